@@ -1,0 +1,136 @@
+"""ctypes binding of libsqp.so (see include/sqp.h for the contract of each call).
+
+Same names as the C entry points without the ``sqp_`` prefix.  Tensors must live on
+the GPU, be contiguous and have the dtype the C ABI expects; outputs are allocated
+with torch (device memory plumbing only) unless passed in.
+"""
+import ctypes
+import os
+
+import torch  # also makes sure the process-wide HIP runtime is the one torch uses
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsqp.so")
+
+EXPORTS = ["sqp_status_string", "sqp_smooth_scales", "sqp_smooth_apply_x", "sqp_smooth_apply_w",
+           "sqp_quantize_pack", "sqp_dequantize", "sqp_w4a16_gemm"]
+
+
+class SqpError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib():
+    """Load libsqp.so (built beforehand by paper_2312_03788_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise SqpError("libsqp.so is not built: run `python -m paper_2312_03788_amd.build`")
+        L = ctypes.CDLL(_LIB_PATH)
+        L.sqp_status_string.restype = ctypes.c_char_p
+        L.sqp_status_string.argtypes = [ctypes.c_int]
+        vp, i, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+        L.sqp_smooth_scales.argtypes = [i, i, i, f, vp, vp, vp, vp]
+        L.sqp_smooth_apply_x.argtypes = [i, i, vp, vp, vp, vp]
+        L.sqp_smooth_apply_w.argtypes = [i, i, vp, vp, vp, vp]
+        L.sqp_quantize_pack.argtypes = [i, i, i, vp, vp, vp, vp, vp]
+        L.sqp_dequantize.argtypes = [i, i, i, vp, vp, vp, vp, vp]
+        L.sqp_w4a16_gemm.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp]
+        for name in EXPORTS[1:]:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise SqpError("%s failed: %s (%d)" % (what, lib().sqp_status_string(rc).decode(), rc))
+
+
+def _dev(t, dtype, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda):
+        raise SqpError("%s must be a GPU tensor" % name)
+    if t.dtype != dtype:
+        raise SqpError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise SqpError("%s must be contiguous" % name)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def smooth_scales(x_cal, w, alpha, out=None):
+    """Eq. 6: s [K] fp32 from calibration activations x_cal [T,K] and weight w [K,N]."""
+    T, K = x_cal.shape
+    K2, N = w.shape
+    if K != K2:
+        raise SqpError("x_cal and w disagree on K")
+    s = out if out is not None else torch.empty(K, dtype=torch.float32, device=w.device)
+    _check(lib().sqp_smooth_scales(T, K, N, float(alpha), _dev(x_cal, torch.float16, "x_cal"),
+                                   _dev(w, torch.float16, "w"), _dev(s, torch.float32, "s"), _stream()),
+           "sqp_smooth_scales")
+    return s
+
+
+def smooth_apply_x(x, s, out=None):
+    """Eq. 5, activation side: x / s per input channel."""
+    M, K = x.shape
+    o = out if out is not None else torch.empty_like(x)
+    _check(lib().sqp_smooth_apply_x(M, K, _dev(x, torch.float16, "x"), _dev(s, torch.float32, "s"),
+                                    _dev(o, torch.float16, "x_out"), _stream()), "sqp_smooth_apply_x")
+    return o
+
+
+def smooth_apply_w(w, s, out=None):
+    """Eq. 5, weight side: s * w per input channel."""
+    K, N = w.shape
+    o = out if out is not None else torch.empty_like(w)
+    _check(lib().sqp_smooth_apply_w(K, N, _dev(w, torch.float16, "w"), _dev(s, torch.float32, "s"),
+                                    _dev(o, torch.float16, "w_out"), _stream()), "sqp_smooth_apply_w")
+    return o
+
+
+def quantize_pack(w, group=128, out=None):
+    """Eq. 1 group-wise along K: returns (packed int32 [K/8,N] holding the uint32 words,
+    scales fp16 [K/group,N], zeros uint8 [K/group,N])."""
+    K, N = w.shape
+    if out is not None:
+        packed, scales, zeros = out
+    else:
+        if group <= 0 or K % max(group, 1):
+            raise SqpError("K must be a multiple of group")
+        packed = torch.empty((K // 8, N), dtype=torch.int32, device=w.device)
+        scales = torch.empty((K // group, N), dtype=torch.float16, device=w.device)
+        zeros = torch.empty((K // group, N), dtype=torch.uint8, device=w.device)
+    _check(lib().sqp_quantize_pack(N, K, group, _dev(w, torch.float16, "w"), _dev(packed, torch.int32, "packed"),
+                                   _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
+                                   _stream()), "sqp_quantize_pack")
+    return packed, scales, zeros
+
+
+def dequantize(packed, scales, zeros, group=128, out=None):
+    """Second line of Eq. 1: w_hat fp16 [K,N]."""
+    K, N = packed.shape[0] * 8, packed.shape[1]
+    o = out if out is not None else torch.empty((K, N), dtype=torch.float16, device=packed.device)
+    _check(lib().sqp_dequantize(N, K, group, _dev(packed, torch.int32, "packed"), _dev(scales, torch.float16, "scales"),
+                                _dev(zeros, torch.uint8, "zeros"), _dev(o, torch.float16, "w_hat"), _stream()),
+           "sqp_dequantize")
+    return o
+
+
+def w4a16_gemm(x, packed, scales, zeros, group=128, out=None):
+    """Eq. 3: y [M,N] fp16 = x [M,K] fp16 times the group-wise 4-bit weight."""
+    M, K = x.shape
+    N = packed.shape[1]
+    if packed.shape[0] * 8 != K:
+        raise SqpError("x and packed disagree on K")
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _check(lib().sqp_w4a16_gemm(M, N, K, group, _dev(x, torch.float16, "x"), _dev(packed, torch.int32, "packed"),
+                                _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
+                                _dev(y, torch.float16, "y"), _stream()), "sqp_w4a16_gemm")
+    return y

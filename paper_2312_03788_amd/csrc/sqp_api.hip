@@ -1,0 +1,39 @@
+// Entry point of the quantised linear layer (Eq. 3 of arXiv 2312.03788): argument checks
+// and the choice between the weight-streaming path (small M) and the tiled matrix-core
+// path (large M).
+#include "sqp_common.h"
+
+extern "C" const char *sqp_status_string(int status)
+{
+    switch (status) {
+        case SQP_OK: return "ok";
+        case SQP_ERR_NULL: return "null pointer";
+        case SQP_ERR_SHAPE: return "shape rule violated";
+        case SQP_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case SQP_ERR_ARG: return "argument out of range";
+        case SQP_ERR_LAUNCH: return "HIP launch error";
+        case SQP_ERR_WORKSPACE: return "device workspace unavailable";
+        default: return "unknown status";
+    }
+}
+
+static int g_decode_max_m = 64;
+// Test/benchmark hook: rows up to which the weight-streaming path is used.
+extern "C" void sqp_debug_set_decode_max_m(int m) { g_decode_max_m = m; }
+
+extern "C" int sqp_w4a16_gemm(int M, int N, int K, int group, const void *x, const uint32_t *packed,
+                              const void *scales, const uint8_t *zeros, void *y, void *stream)
+{
+    if (!x || !packed || !scales || !zeros || !y) return SQP_ERR_NULL;
+    if (M <= 0) return SQP_ERR_SHAPE;
+    int rc = sqp_check_quant_shape(N, K, group);
+    if (rc) return rc;
+    if (sqp_misaligned(x) || sqp_misaligned(packed) || sqp_misaligned(scales) || sqp_misaligned(zeros) || sqp_misaligned(y))
+        return SQP_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    const h16 *xp = (const h16 *)x;
+    const h16 *sp = (const h16 *)scales;
+    h16 *yp = (h16 *)y;
+    if (M <= g_decode_max_m && M <= 64) return sqp_gemm_decode(M, N, K, group, xp, packed, sp, zeros, yp, st);
+    return sqp_gemm_prefill(M, N, K, group, xp, packed, sp, zeros, yp, st);
+}

@@ -1,0 +1,320 @@
+// Companion kernels of the W4A16 layer: smoothing factors (Eq. 6), smoothing of
+// activations and weights (Eq. 5), group-wise 4-bit quantise + pack and dequantise
+// (Eq. 1, Sec 2.2) of arXiv 2312.03788.  All are single streaming passes, bound by HBM
+// bandwidth; every result here is defined bit-exactly (IEEE fp32 divide/multiply, one
+// round-to-nearest-even to fp16), so no fast-math and no FMA contraction in this file.
+#include "sqp_common.h"
+
+#pragma clang fp contract(off)
+
+namespace {
+
+__device__ __forceinline__ float h2f_lo(uint32_t v) { return (float)__builtin_bit_cast(h16x2, v).x; }
+__device__ __forceinline__ float h2f_hi(uint32_t v) { return (float)__builtin_bit_cast(h16x2, v).y; }
+__device__ __forceinline__ uint32_t pack_h2(float a, float b)
+{
+    h16x2 r;
+    r.x = (h16)a;
+    r.y = (h16)b;
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// ------------------------------------------------------------------ Eq. 6
+
+__global__ void fill_zero_u32(uint32_t *p, int n)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// max_t |x[t][j]|, accumulated into ax_bits[j] as the bit pattern of a non-negative
+// float (unsigned order == float order there), so the atomic max is order-independent.
+// Block: 32 column-octets x 8 row lanes.
+__global__ void __launch_bounds__(256) absmax_x_kernel(int T, int K, const uint4 *x, uint32_t *ax_bits)
+{
+    __shared__ float red[8][256];
+    const int oct = threadIdx.x & 31, rl = threadIdx.x >> 5;
+    const int koct = blockIdx.x * 32 + oct;  // column octet
+    const int KO = K >> 3;
+    float m[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) m[i] = 0.0f;
+    if (koct < KO) {
+        for (int t = blockIdx.y * 8 + rl; t < T; t += 8 * gridDim.y) {
+            uint4 v = x[(size_t)t * KO + koct];
+            uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                m[2 * i] = fmaxf(m[2 * i], fabsf(h2f_lo(w[i])));
+                m[2 * i + 1] = fmaxf(m[2 * i + 1], fabsf(h2f_hi(w[i])));
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i++) red[rl][oct * 8 + i] = m[i];
+    __syncthreads();
+    const int col = blockIdx.x * 256 + threadIdx.x;
+    if (col < K) {
+        float r = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; i++) r = fmaxf(r, red[i][threadIdx.x]);
+        atomicMax(&ax_bits[col], __builtin_bit_cast(uint32_t, r));
+    }
+}
+
+// One block per input channel j: aw = max_n |w[j][n]|, then Eq. 6 with ax read from
+// s[j] (left there by absmax_x_kernel) and s[j] overwritten with the factor.
+__global__ void __launch_bounds__(256) absmax_w_factor_kernel(int N, float alpha, const uint4 *w, float *s)
+{
+    __shared__ float red[4];
+    const int j = blockIdx.x;
+    const int NO = N >> 3;
+    const uint4 *row = w + (size_t)j * NO;
+    float m = 0.0f;
+    for (int o = threadIdx.x; o < NO; o += 256) {
+        uint4 v = row[o];
+        uint32_t q[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; i++) m = fmaxf(m, fmaxf(fabsf(h2f_lo(q[i])), fabsf(h2f_hi(q[i]))));
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float aw = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        float ax = s[j];
+        ax = ax > 1e-5f ? ax : 1e-5f;
+        aw = aw > 1e-5f ? aw : 1e-5f;
+        double a = (double)alpha;
+        s[j] = (float)(pow((double)ax, a) / pow((double)aw, 1.0 - a));
+    }
+}
+
+// ------------------------------------------------------------------ Eq. 5
+
+__global__ void __launch_bounds__(256) apply_x_kernel(long total_oct, int KO, const uint4 *x, const float4 *s, uint4 *out)
+{
+    long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total_oct) return;
+    int ko = (int)(i % KO);
+    uint4 v = x[i];
+    float4 s0 = s[2 * ko], s1 = s[2 * ko + 1];
+    uint4 r;
+    r.x = pack_h2(h2f_lo(v.x) / s0.x, h2f_hi(v.x) / s0.y);
+    r.y = pack_h2(h2f_lo(v.y) / s0.z, h2f_hi(v.y) / s0.w);
+    r.z = pack_h2(h2f_lo(v.z) / s1.x, h2f_hi(v.z) / s1.y);
+    r.w = pack_h2(h2f_lo(v.w) / s1.z, h2f_hi(v.w) / s1.w);
+    out[i] = r;
+}
+
+__global__ void __launch_bounds__(256) apply_w_kernel(long total_oct, int NO, const uint4 *w, const float *s, uint4 *out)
+{
+    long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total_oct) return;
+    float sj = s[i / NO];
+    uint4 v = w[i];
+    uint4 r;
+    r.x = pack_h2(sj * h2f_lo(v.x), sj * h2f_hi(v.x));
+    r.y = pack_h2(sj * h2f_lo(v.y), sj * h2f_hi(v.y));
+    r.z = pack_h2(sj * h2f_lo(v.z), sj * h2f_hi(v.z));
+    r.w = pack_h2(sj * h2f_lo(v.w), sj * h2f_hi(v.w));
+    out[i] = r;
+}
+
+// ------------------------------------------------------------------ Eq. 1
+
+struct GroupParams {
+    float d;     // the fp16-rounded step, as float
+    uint16_t d16;
+    int z;
+};
+
+__device__ __forceinline__ GroupParams group_params(float wmin, float wmax)
+{
+    float lo = wmin < 0.0f ? wmin : 0.0f;
+    float hi = wmax > 0.0f ? wmax : 0.0f;
+    float d32 = (hi - lo) / 15.0f;
+    h16 dh = (h16)d32;
+    uint16_t bits = __builtin_bit_cast(uint16_t, dh);
+    if ((bits & 0x7fffu) == 0) bits = 0x0001u;
+    GroupParams p;
+    p.d16 = bits;
+    p.d = (float)__builtin_bit_cast(h16, bits);
+    int z = (int)rintf(-lo / p.d);
+    p.z = z < 0 ? 0 : (z > 15 ? 15 : z);
+    return p;
+}
+
+__device__ __forceinline__ uint32_t code_of(float v, const GroupParams &p)
+{
+    int q = (int)rintf(v / p.d) + p.z;
+    q = q < 0 ? 0 : (q > 15 ? 15 : q);
+    return (uint32_t)q;
+}
+
+// One thread quantises one group of G rows of two adjacent columns; the 2*G weights
+// stay in registers between the min/max pass and the coding pass.
+// grid: (ceil(N/512), K/G), block 256.
+template <int G>
+__global__ void __launch_bounds__(256) quantize_pack_reg_kernel(int N, const uint32_t *w, uint2 *packed, uint32_t *scales, uint16_t *zeros)
+{
+    const int n2 = blockIdx.x * 256 + threadIdx.x;
+    const int N2 = N >> 1;
+    if (n2 >= N2) return;
+    const int t = blockIdx.y;
+    const uint32_t *wp = w + (size_t)t * G * N2 + n2;
+    uint32_t v[G];
+#pragma unroll
+    for (int i = 0; i < G; i++) v[i] = wp[(size_t)i * N2];
+    float mn0 = h2f_lo(v[0]), mx0 = mn0, mn1 = h2f_hi(v[0]), mx1 = mn1;
+#pragma unroll
+    for (int i = 1; i < G; i++) {
+        float a = h2f_lo(v[i]), b = h2f_hi(v[i]);
+        mn0 = fminf(mn0, a);
+        mx0 = fmaxf(mx0, a);
+        mn1 = fminf(mn1, b);
+        mx1 = fmaxf(mx1, b);
+    }
+    GroupParams p0 = group_params(mn0, mx0), p1 = group_params(mn1, mx1);
+    scales[(size_t)t * N2 + n2] = (uint32_t)p0.d16 | ((uint32_t)p1.d16 << 16);
+    zeros[(size_t)t * N2 + n2] = (uint16_t)(p0.z | (p1.z << 8));
+    uint2 *pp = packed + (size_t)t * (G / 8) * N2 + n2;
+#pragma unroll
+    for (int j = 0; j < G / 8; j++) {
+        uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            w0 |= code_of(h2f_lo(v[8 * j + i]), p0) << (4 * i);
+            w1 |= code_of(h2f_hi(v[8 * j + i]), p1) << (4 * i);
+        }
+        pp[(size_t)j * N2] = make_uint2(w0, w1);
+    }
+}
+
+// Any group size (multiple of 8): the group is read twice.
+__global__ void __launch_bounds__(256) quantize_pack_any_kernel(int N, int G, const uint32_t *w, uint2 *packed, uint32_t *scales, uint16_t *zeros)
+{
+    const int n2 = blockIdx.x * 256 + threadIdx.x;
+    const int N2 = N >> 1;
+    if (n2 >= N2) return;
+    const int t = blockIdx.y;
+    const uint32_t *wp = w + (size_t)t * G * N2 + n2;
+    uint32_t v0 = wp[0];
+    float mn0 = h2f_lo(v0), mx0 = mn0, mn1 = h2f_hi(v0), mx1 = mn1;
+    for (int i = 1; i < G; i++) {
+        uint32_t v = wp[(size_t)i * N2];
+        float a = h2f_lo(v), b = h2f_hi(v);
+        mn0 = fminf(mn0, a);
+        mx0 = fmaxf(mx0, a);
+        mn1 = fminf(mn1, b);
+        mx1 = fmaxf(mx1, b);
+    }
+    GroupParams p0 = group_params(mn0, mx0), p1 = group_params(mn1, mx1);
+    scales[(size_t)t * N2 + n2] = (uint32_t)p0.d16 | ((uint32_t)p1.d16 << 16);
+    zeros[(size_t)t * N2 + n2] = (uint16_t)(p0.z | (p1.z << 8));
+    uint2 *pp = packed + (size_t)t * (G / 8) * N2 + n2;
+    for (int j = 0; j < G / 8; j++) {
+        uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            uint32_t v = wp[(size_t)(8 * j + i) * N2];
+            w0 |= code_of(h2f_lo(v), p0) << (4 * i);
+            w1 |= code_of(h2f_hi(v), p1) << (4 * i);
+        }
+        pp[(size_t)j * N2] = make_uint2(w0, w1);
+    }
+}
+
+// One thread expands one packed word of two adjacent columns into 8 rows.
+// grid: (ceil(N/512), K/8), block 256.
+__global__ void __launch_bounds__(256) dequantize_kernel(int N, int words_per_group, const uint2 *packed, const uint32_t *scales, const uint16_t *zeros, uint32_t *w_hat)
+{
+    const int n2 = blockIdx.x * 256 + threadIdx.x;
+    const int N2 = N >> 1;
+    if (n2 >= N2) return;
+    const int j = blockIdx.y;
+    const int t = j / words_per_group;
+    uint2 pw = packed[(size_t)j * N2 + n2];
+    uint32_t sc = scales[(size_t)t * N2 + n2];
+    uint16_t zz = zeros[(size_t)t * N2 + n2];
+    float d0 = h2f_lo(sc), d1 = h2f_hi(sc);
+    int z0 = zz & 0xff, z1 = zz >> 8;
+    uint32_t *out = w_hat + (size_t)j * 8 * N2 + n2;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        int q0 = (int)((pw.x >> (4 * i)) & 15u), q1 = (int)((pw.y >> (4 * i)) & 15u);
+        out[(size_t)i * N2] = pack_h2((float)(q0 - z0) * d0, (float)(q1 - z1) * d1);
+    }
+}
+
+}  // namespace
+
+extern "C" int sqp_smooth_scales(int T, int K, int N, float alpha, const void *x_cal, const void *w, float *s, void *stream)
+{
+    if (!x_cal || !w || !s) return SQP_ERR_NULL;
+    if (T <= 0 || K <= 0 || N <= 0 || (K % 8) || (N % 8)) return SQP_ERR_SHAPE;
+    if (sqp_misaligned(x_cal) || sqp_misaligned(w) || sqp_misaligned(s)) return SQP_ERR_ALIGN;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return SQP_ERR_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    fill_zero_u32<<<(K + 255) / 256, 256, 0, st>>>((uint32_t *)s, K);
+    int gy = (T + 63) / 64;
+    if (gy > 64) gy = 64;
+    absmax_x_kernel<<<dim3((K + 255) / 256, gy), 256, 0, st>>>(T, K, (const uint4 *)x_cal, (uint32_t *)s);
+    absmax_w_factor_kernel<<<K, 256, 0, st>>>(N, alpha, (const uint4 *)w, s);
+    return sqp_launch_status();
+}
+
+extern "C" int sqp_smooth_apply_x(int M, int K, const void *x, const float *s, void *x_out, void *stream)
+{
+    if (!x || !s || !x_out) return SQP_ERR_NULL;
+    if (M <= 0 || K <= 0 || (K % 8)) return SQP_ERR_SHAPE;
+    if (sqp_misaligned(x) || sqp_misaligned(s) || sqp_misaligned(x_out)) return SQP_ERR_ALIGN;
+    long total = (long)M * (K / 8);
+    apply_x_kernel<<<(unsigned)((total + 255) / 256), 256, 0, (hipStream_t)stream>>>(total, K / 8, (const uint4 *)x, (const float4 *)s, (uint4 *)x_out);
+    return sqp_launch_status();
+}
+
+extern "C" int sqp_smooth_apply_w(int K, int N, const void *w, const float *s, void *w_out, void *stream)
+{
+    if (!w || !s || !w_out) return SQP_ERR_NULL;
+    if (K <= 0 || N <= 0 || (N % 8)) return SQP_ERR_SHAPE;
+    if (sqp_misaligned(w) || sqp_misaligned(s) || sqp_misaligned(w_out)) return SQP_ERR_ALIGN;
+    long total = (long)K * (N / 8);
+    apply_w_kernel<<<(unsigned)((total + 255) / 256), 256, 0, (hipStream_t)stream>>>(total, N / 8, (const uint4 *)w, s, (uint4 *)w_out);
+    return sqp_launch_status();
+}
+
+extern "C" int sqp_quantize_pack(int N, int K, int group, const void *w, uint32_t *packed, void *scales, uint8_t *zeros, void *stream)
+{
+    if (!w || !packed || !scales || !zeros) return SQP_ERR_NULL;
+    int rc = sqp_check_quant_shape(N, K, group);
+    if (rc) return rc;
+    if (K / group > 65535) return SQP_ERR_SHAPE;
+    if (sqp_misaligned(w) || sqp_misaligned(packed) || sqp_misaligned(scales) || sqp_misaligned(zeros)) return SQP_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    dim3 grid((N / 2 + 255) / 256, K / group);
+    const uint32_t *wp = (const uint32_t *)w;
+    uint2 *pp = (uint2 *)packed;
+    uint32_t *sp = (uint32_t *)scales;
+    uint16_t *zp = (uint16_t *)zeros;
+    switch (group) {
+        case 32: quantize_pack_reg_kernel<32><<<grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
+        case 64: quantize_pack_reg_kernel<64><<<grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
+        case 128: quantize_pack_reg_kernel<128><<<grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
+        default: quantize_pack_any_kernel<<<grid, 256, 0, st>>>(N, group, wp, pp, sp, zp); break;
+    }
+    return sqp_launch_status();
+}
+
+extern "C" int sqp_dequantize(int N, int K, int group, const uint32_t *packed, const void *scales, const uint8_t *zeros, void *w_hat, void *stream)
+{
+    if (!packed || !scales || !zeros || !w_hat) return SQP_ERR_NULL;
+    int rc = sqp_check_quant_shape(N, K, group);
+    if (rc) return rc;
+    if (K / 8 > 65535) return SQP_ERR_SHAPE;
+    if (sqp_misaligned(packed) || sqp_misaligned(scales) || sqp_misaligned(zeros) || sqp_misaligned(w_hat)) return SQP_ERR_ALIGN;
+    dim3 grid((N / 2 + 255) / 256, K / 8);
+    dequantize_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(N, group / 8, (const uint2 *)packed, (const uint32_t *)scales, (const uint16_t *)zeros, (uint32_t *)w_hat);
+    return sqp_launch_status();
+}

@@ -1,0 +1,71 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2312_03788_amd as sqp
+    return sqp.lib()
+
+
+def test_exports_match_header(L):
+    hdr = open(os.path.join(ROOT, "include", "sqp.h")).read()
+    declared = set(re.findall(r"\b(sqp_[a-z0-9_]+)\s*\(", hdr))
+    assert {"sqp_smooth_scales", "sqp_smooth_apply_x", "sqp_smooth_apply_w", "sqp_quantize_pack",
+            "sqp_dequantize", "sqp_w4a16_gemm", "sqp_status_string"} <= declared
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings(L):
+    assert L.sqp_status_string(0) == b"ok"
+    for code in range(-6, 0):
+        assert L.sqp_status_string(code) not in (b"ok", b"unknown status")
+
+
+def test_argument_errors(L):
+    P = ctypes.c_void_p
+    good = P(0x1000)
+    odd = P(0x1008)
+    null = P(0)
+    # sqp_w4a16_gemm(M,N,K,group,x,packed,scales,zeros,y,stream)
+    g = L.sqp_w4a16_gemm
+    assert g(4, 1024, 1024, 128, null, good, good, good, good, null) == -1
+    assert g(0, 1024, 1024, 128, good, good, good, good, good, null) == -2
+    assert g(4, 1020, 1024, 128, good, good, good, good, good, null) == -2  # N % 8
+    assert g(4, 1024, 1000, 128, good, good, good, good, good, null) == -2  # K % group
+    assert g(4, 1024, 1024, 12, good, good, good, good, good, null) == -2   # group % 8
+    assert g(4, 1024, 1024, 128, good, odd, good, good, good, null) == -3
+    q = L.sqp_quantize_pack
+    assert q(1024, 1024, 128, good, good, good, null, null) == -1
+    assert q(1024, 1024, 100, good, good, good, good, null) == -2
+    assert q(1024, 1024, 128, odd, good, good, good, null) == -3
+    d = L.sqp_dequantize
+    assert d(1024, 1024, 128, good, good, good, null, null) == -1
+    assert d(1024, 1028, 128, good, good, good, good, null) == -2
+    s = L.sqp_smooth_scales
+    assert s(8, 1024, 1024, ctypes.c_float(0.5), null, good, good, null) == -1
+    assert s(8, 1024, 1024, ctypes.c_float(1.5), good, good, good, null) == -4
+    assert s(8, 1024, 1024, ctypes.c_float(float("nan")), good, good, good, null) == -4
+    assert s(8, 1021, 1024, ctypes.c_float(0.5), good, good, good, null) == -2
+    assert L.sqp_smooth_apply_x(4, 1024, good, good, odd, null) == -3
+    assert L.sqp_smooth_apply_w(1024, 1020, good, good, good, null) == -2
+
+
+def test_product_does_not_import_oracle():
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r); import paper_2312_03788_amd; "
+            "assert 'oracle' not in sys.modules" % ROOT)
+    subprocess.run([sys.executable, "-c", code], check=True)
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "paper_2312_03788_amd")):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                assert "oracle" not in open(os.path.join(dirpath, f)).read(), f

@@ -1,0 +1,127 @@
+"""GPU parity for the W4A16 GEMM (Eq. 3) against the oracle's fp64 definition:
+|y_gpu - y_ref| <= 1e-3 * sum_k|x_k w_hat_k| + 1 fp16 ulp per element."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import dev, gemm_tolerance_ok, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sqp():
+    import paper_2312_03788_amd as m
+    m.lib()
+    return m
+
+
+def _layer(orc, M, K, N, group, shape_idx=0):
+    """Smoothed + quantised layer operands from the oracle (numpy)."""
+    x, xcal, w = wl.layer_inputs(M, K, N, shape_idx=shape_idx)
+    s = orc.smooth_scales(xcal, w, wl.ALPHA)
+    xs = orc.smooth_apply_x(x, s)
+    ws = orc.smooth_apply_w(w, s)
+    p, sc, z = orc.quantize_pack(ws, group)
+    return xs, p, sc, z
+
+
+def _check(orc, sqp, xs, p, sc, z, group):
+    y_ref, t_ref = orc.w4a16_gemm_ref(xs, p, sc, z, group)
+    y = host(sqp.w4a16_gemm(dev(xs), dev(p), dev(sc), dev(z), group))
+    torch.cuda.synchronize()
+    ok, worst, nbad = gemm_tolerance_ok(orc, y, y_ref, t_ref)
+    assert ok, "worst err/tol %.3f, %d elements out of tolerance" % (worst, nbad)
+    return y
+
+
+def test_cfg1_single_layer(orc, sqp):
+    """M=4, K=N=1024, group 128, alpha=0.5, outlier channels."""
+    print("case cfg1", flush=True)
+    xs, p, sc, z = _layer(orc, 4, 1024, 1024, 128)
+    _check(orc, sqp, xs, p, sc, z, 128)
+
+
+@pytest.mark.parametrize("M", [1, 2, 7, 8, 15, 16, 17, 31, 32, 33, 48, 63, 64])
+def test_decode_row_counts(orc, sqp, M):
+    print("case rows", M, flush=True)
+    xs, p, sc, z = _layer(orc, M, 512, 192, 128)
+    _check(orc, sqp, xs, p, sc, z, 128)
+
+
+@pytest.mark.parametrize("M,K,N,group", [
+    (3, 128, 8, 128), (5, 256, 72, 128), (16, 384, 520, 128), (9, 1152, 200, 128), (4, 256, 64, 32),
+    (16, 320, 136, 64), (33, 1024, 264, 256), (2, 48, 24, 24), (6, 64, 16, 8), (64, 2048, 1000, 128)])
+def test_decode_ragged_shapes(orc, sqp, M, K, N, group):
+    print("case ragged", M, K, N, group, flush=True)
+    xs, p, sc, z = _layer(orc, M, K, N, group)
+    _check(orc, sqp, xs, p, sc, z, group)
+
+
+@pytest.mark.parametrize("split", [1, 2, 3, 5, 8])
+def test_decode_split_k_deterministic(orc, sqp, split):
+    """Every K split gives an in-tolerance result, and repeated runs are bit-identical."""
+    print("case split", split, flush=True)
+    L = sqp.lib()
+    xs, p, sc, z = _layer(orc, 16, 2048, 328, 128)
+    L.sqp_debug_set_decode_split(split)
+    try:
+        y0 = _check(orc, sqp, xs, p, sc, z, 128)
+        for _ in range(3):
+            y1 = _check(orc, sqp, xs, p, sc, z, 128)
+            assert np.array_equal(y0.view(np.uint16), y1.view(np.uint16))
+    finally:
+        L.sqp_debug_set_decode_split(0)
+
+
+def test_integer_exact(orc, sqp):
+    """step = 1, Z = 0, small integer activations: every partial sum is an exact integer in
+    fp32, so the GPU result must equal the integer product exactly."""
+    rng = np.random.Generator(np.random.PCG64(3))
+    M, N, K, g = 16, 96, 512, 128
+    q = rng.integers(0, 16, size=(K, N))
+    x = rng.integers(-4, 5, size=(M, K))
+    p = np.zeros((K // 8, N), np.uint32)
+    for i in range(8):
+        p |= q[i::8].astype(np.uint32) << np.uint32(4 * i)
+    ones = np.ones((K // g, N), np.float16)
+    zz = np.zeros((K // g, N), np.uint8)
+    y = host(sqp.w4a16_gemm(dev(x.astype(np.float16)), dev(p), dev(ones), dev(zz), g))
+    assert np.array_equal(y.astype(np.int64), x @ q)
+
+
+def test_tiny_activations(orc, sqp):
+    """Activations in the fp16 subnormal range still meet the tolerance."""
+    xs, p, sc, z = _layer(orc, 8, 512, 128, 128)
+    xs = (xs.astype(np.float32) * 2.0 ** -16).astype(np.float16)
+    _check(orc, sqp, xs, p, sc, z, 128)
+
+
+@pytest.mark.parametrize("shape_idx", [0, 1, 2, 3])
+@pytest.mark.parametrize("M", [1, 8, 16])
+def test_cfg2_7b_shapes(orc, sqp, shape_idx, M):
+    """Code Llama-7B layer shapes at decode row counts, full-output parity."""
+    K, N = wl.MODEL_SHAPES["7b"][shape_idx]
+    print("case 7b", K, N, M, flush=True)
+    xs, p, sc, z = _layer_cached(orc, M, K, N, shape_idx)
+    _check(orc, sqp, xs, p, sc, z, 128)
+
+
+_cache = {}
+
+
+def _layer_cached(orc, M, K, N, shape_idx):
+    """Quantise each big weight once per session (the oracle quantiser is slow)."""
+    key = (K, N, shape_idx)
+    if key not in _cache:
+        _, xcal, w = wl.layer_inputs(1, K, N, shape_idx=shape_idx)
+        s = orc.smooth_scales(xcal, w, wl.ALPHA)
+        ws = orc.smooth_apply_w(w, s)
+        _cache.clear()
+        _cache[key] = (s,) + orc.quantize_pack(ws, 128)
+    s, p, sc, z = _cache[key]
+    x = wl.activation(M, K, seed=2000 + M)
+    return orc.smooth_apply_x(x, s), p, sc, z
