@@ -10,7 +10,7 @@ import os
 import torch  # also makes sure the process-wide HIP runtime is the one torch uses
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libsqp.so")
+_LIB_PATH = os.environ.get("SQP_LIBRARY", os.path.join(_HERE, "libsqp.so"))  # override: another build
 
 EXPORTS = ["sqp_status_string", "sqp_smooth_scales", "sqp_smooth_apply_x", "sqp_smooth_apply_w",
            "sqp_quantize_pack", "sqp_dequantize", "sqp_w4a16_gemm"]

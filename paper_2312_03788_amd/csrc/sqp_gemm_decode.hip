@@ -17,9 +17,14 @@
 // SPLIT > 1 workgroups along K, fp32 partial tiles go to a workspace and the workgroup
 // that arrives last (atomic ticket) adds them in split order, so the result does not
 // depend on scheduling.
+#include <type_traits>
+
 #include "sqp_common.h"
 
 namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 template <int VW> struct WVec;
 template <> struct WVec<1> { typedef uint32_t T; };
@@ -59,9 +64,9 @@ __device__ __forceinline__ h16x8 dequant_word(uint32_t w, h16x2 neg_hi, h16x2 ne
 }
 
 // 8 consecutive-k activations (x0..x7 as four dwords) -> the nibble order above.
-__device__ __forceinline__ h16x8 permute_x(const uint4 &v)
+__device__ __forceinline__ h16x8 permute_x(const u32x4 &v)
 {
-    uint4 p;
+    u32x4 p;
     p.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);  // (x0, x4)
     p.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);  // (x1, x5)
     p.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);  // (x2, x6)
@@ -76,10 +81,12 @@ struct Workspace {
 
 // MT: 16-row tiles of x (M <= 16*MT).  VW: packed words per lane per load.  NT: loads per
 // k-step (strip width 16*VW*NT).  NW: waves per workgroup.  KSPG: k-steps (of 32) per
-// quantisation group.
-template <int MT, int VW, int NT, int NW, int KSPG>
+// chunk; a quantisation group is cpg chunks (cpg = 1 unless the group is a multiple of
+// 128 above 128).  D: register stages of packed weights (groups in flight + 1).
+// XD: LDS stages of activations per wave.
+template <int MT, int VW, int NT, int NW, int KSPG, int D, int XD>
 __global__ void __launch_bounds__(NW * 64)
-w4a16_decode_kernel(int M, int N, int K, const h16 *__restrict__ x, const uint32_t *__restrict__ packed,
+w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, const uint32_t *__restrict__ packed,
                     const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y,
                     Workspace ws)
 {
@@ -87,10 +94,19 @@ w4a16_decode_kernel(int M, int N, int K, const h16 *__restrict__ x, const uint32
     constexpr int NTILE = NT * VW;        // 16x16 accumulator tiles per m-tile
     constexpr int REGS = MT * NTILE * 4;  // fp32 accumulator registers per lane
     constexpr int BN = 16 * VW * NT;      // strip width
-    __shared__ float red[NW][REGS][64];
+    // Activations reach the matrix cores through a per-wave LDS ring filled by direct
+    // global->LDS loads (no registers held while they are in flight); the same LDS is
+    // reused for the cross-wave sum at the end.
+    constexpr int XSTAGE = KSPG * MT * 1024;  // bytes: one group of x for this wave
+    constexpr int XRING = XD * XSTAGE;
+    constexpr int RED_BYTES = NW * REGS * 64 * 4;
+    constexpr int SMEM = NW * XRING > RED_BYTES ? NW * XRING : RED_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
     __shared__ unsigned ticket_s;
+    float(*red)[REGS][64] = reinterpret_cast<float(*)[REGS][64]>(smem);
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept scalar
     const int lc = lane & 15, lk = lane >> 4;
     const int n0 = blockIdx.x * BN;
     const int split = gridDim.y, sidx = blockIdx.y;
@@ -98,20 +114,21 @@ w4a16_decode_kernel(int M, int N, int K, const h16 *__restrict__ x, const uint32
     // this workgroup's group range, then this wave's share of it
     const int gb0 = (int)((long)groups * sidx / split), gb1 = (int)((long)groups * (sidx + 1) / split);
     const int g0 = gb0 + (gb1 - gb0) * wave / NW, g1 = gb0 + (gb1 - gb0) * (wave + 1) / NW;
+    unsigned char *xring = smem + wave * XRING;
 
+    // lanes past the last column read column 0 instead; their results are never stored
     int ncol[NT];
-    bool nok[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; nt++) {
         ncol[nt] = n0 + nt * 16 * VW + VW * lc;
-        nok[nt] = ncol[nt] < N;
-        if (!nok[nt]) ncol[nt] = 0;
+        if (ncol[nt] >= N) ncol[nt] = 0;
     }
-    int xrow[MT];
+    const h16 *xsrc[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; mt++) {
         int m = mt * 16 + lc;
-        xrow[mt] = m < M ? m : M - 1;
+        m = m < M ? m : M - 1;
+        xsrc[mt] = x + (size_t)m * K + lk * 8;
     }
 
     f32x4 acc[MT][NTILE];
@@ -120,44 +137,65 @@ w4a16_decode_kernel(int M, int N, int K, const h16 *__restrict__ x, const uint32
 #pragma unroll
         for (int t = 0; t < NTILE; t++) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    static_assert(VW == 4, "one dwordx4 of packed words per lane");
     struct Stage {
-        wvec w[KSPG][NT];
-        uint4 xa[KSPG][MT];
-        uint32_t sc[NT][(VW + 1) / 2];  // VW fp16 steps
-        uint32_t zr[NT];                // VW zero points, one byte each
+        u32x4 w[KSPG][NT];
+        u32x2 sc[NT];     // 4 fp16 steps
+        uint32_t zr[NT];  // 4 zero points, one byte each
     };
 
-    auto issue = [&](Stage &s, int g) {
+    // The weight, step and zero-point loads are written in assembly so that this kernel, not
+    // the compiler, decides when to wait for them: the registers of a stage must not be read
+    // before the s_waitcnt issued by `landed` below.
+    auto issue_w = [&](Stage &s, int g) {
 #pragma unroll
         for (int ks = 0; ks < KSPG; ks++) {
             const int row = (g * KSPG + ks) * 4 + lk;  // packed row = k / 8
 #pragma unroll
-            for (int nt = 0; nt < NT; nt++)
-                s.w[ks][nt] = nok[nt] ? *reinterpret_cast<const wvec *>(packed + (size_t)row * N + ncol[nt]) : wzero<VW>();
-#pragma unroll
-            for (int mt = 0; mt < MT; mt++)
-                s.xa[ks][mt] = *reinterpret_cast<const uint4 *>(x + (size_t)xrow[mt] * K + (size_t)row * 8);
+            for (int nt = 0; nt < NT; nt++) {
+                const uint32_t *p = packed + (size_t)row * N + ncol[nt];
+                asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(s.w[ks][nt]) : "v"(p) : "memory");
+            }
         }
 #pragma unroll
         for (int nt = 0; nt < NT; nt++) {
-            const h16 *sp = scales + (size_t)g * N + ncol[nt];
-            const uint8_t *zp = zeros + (size_t)g * N + ncol[nt];
-            if (VW == 4) {
-                uint2 v = *reinterpret_cast<const uint2 *>(sp);
-                s.sc[nt][0] = v.x;
-                s.sc[nt][(VW + 1) / 2 - 1] = v.y;
-                s.zr[nt] = *reinterpret_cast<const uint32_t *>(zp);
-            } else if (VW == 2) {
-                s.sc[nt][0] = *reinterpret_cast<const uint32_t *>(sp);
-                s.zr[nt] = *reinterpret_cast<const uint16_t *>(zp);
-            } else {
-                s.sc[nt][0] = *reinterpret_cast<const uint16_t *>(sp);
-                s.zr[nt] = *zp;
-            }
+            const int gs = g / cpg;  // quantisation group of this chunk
+            const h16 *sp = scales + (size_t)gs * N + ncol[nt];
+            const uint8_t *zp = zeros + (size_t)gs * N + ncol[nt];
+            asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(s.sc[nt]) : "v"(sp) : "memory");
+            asm volatile("global_load_dword %0, %1, off" : "=v"(s.zr[nt]) : "v"(zp) : "memory");
+        }
+    };
+    // wait until at most `AFTER` loads are outstanding, then tie the stage's registers to the
+    // wait so that no use of them is scheduled ahead of it
+    auto landed = [&](Stage &s, auto after) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(after)::value) : "memory");
+#pragma unroll
+        for (int ks = 0; ks < KSPG; ks++)
+#pragma unroll
+            for (int nt = 0; nt < NT; nt++) asm volatile("" : "+v"(s.w[ks][nt]));
+#pragma unroll
+        for (int nt = 0; nt < NT; nt++) {
+            asm volatile("" : "+v"(s.sc[nt]));
+            asm volatile("" : "+v"(s.zr[nt]));
         }
     };
 
-    auto compute = [&](const Stage &s) {
+    // lane (row lc, k-block lk) copies its 16 bytes of x straight into LDS; the hardware
+    // places lane i at byte 16*i of the destination block, which is where it reads them back.
+    auto issue_x = [&](int slot, int g) {
+#pragma unroll
+        for (int ks = 0; ks < KSPG; ks++)
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                const h16 *src = xsrc[mt] + (size_t)(g * KSPG + ks) * 32;
+                unsigned char *dst = xring + slot * XSTAGE + (ks * MT + mt) * 1024;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                                 (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+            }
+    };
+
+    auto compute = [&](const Stage &s, int slot, bool live) {
         f32x4 accg[MT][NTILE];
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
@@ -176,23 +214,40 @@ w4a16_decode_kernel(int M, int N, int K, const h16 *__restrict__ x, const uint32
                 neg_lo[nt * VW + c] = h16x2{b, b};
                 const uint32_t sw = s.sc[nt][c >> 1];
                 const h16x2 sv = __builtin_bit_cast(h16x2, sw);
-                delta[nt * VW + c] = (float)((c & 1) ? sv.y : sv.x);
+                delta[nt * VW + c] = live ? (float)((c & 1) ? sv.y : sv.x) : 0.f;
             }
+        // The x fragments of the whole group come out of the LDS ring in one go.  The reads
+        // are written in assembly because the compiler cannot tell which ring slot a direct
+        // global->LDS load filled and would otherwise wait for every outstanding load; the
+        // caller has already waited for exactly the loads that filled this slot.
+        const unsigned xs = (unsigned)(size_t)(xring + slot * XSTAGE + lane * 16);
+        constexpr int XB = MT == 1 ? KSPG : 1;  // k-steps fetched from LDS per batch
 #pragma unroll
-        for (int ks = 0; ks < KSPG; ks++) {
-            h16x8 a[MT];
+        for (int kb = 0; kb < KSPG; kb += XB) {
+            u32x4 xa[XB * MT];
 #pragma unroll
-            for (int mt = 0; mt < MT; mt++) a[mt] = permute_x(s.xa[ks][mt]);
+            for (int i = 0; i < XB * MT; i++)
+                asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(xa[i]) : "v"(xs), "n"((kb * MT + i) * 1024) : "memory");
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-            for (int nt = 0; nt < NT; nt++)
+            for (int i = 0; i < XB * MT; i++) asm volatile("" : "+v"(xa[i]));  // no use ahead of the wait
 #pragma unroll
-                for (int c = 0; c < VW; c++) {
-                    const int t = nt * VW + c;
-                    const h16x8 b = dequant_word(wword<VW>(s.w[ks][nt], c), neg_hi[t], neg_lo[t]);
+            for (int kk = 0; kk < XB; kk++) {
+                const int ks = kb + kk;
+                h16x8 a[MT];
 #pragma unroll
-                    for (int mt = 0; mt < MT; mt++)
-                        accg[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b, accg[mt][t], 0, 0, 0);
-                }
+                for (int mt = 0; mt < MT; mt++) a[mt] = permute_x(xa[kk * MT + mt]);
+#pragma unroll
+                for (int nt = 0; nt < NT; nt++)
+#pragma unroll
+                    for (int c = 0; c < VW; c++) {
+                        const int t = nt * VW + c;
+                        const h16x8 b = dequant_word(s.w[ks][nt][c], neg_hi[t], neg_lo[t]);
+#pragma unroll
+                        for (int mt = 0; mt < MT; mt++)
+                            accg[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b, accg[mt][t], 0, 0, 0);
+                    }
+            }
         }
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
@@ -202,16 +257,58 @@ w4a16_decode_kernel(int M, int N, int K, const h16 *__restrict__ x, const uint32
                 for (int r = 0; r < 4; r++) acc[mt][t][r] = fmaf(delta[t], accg[mt][t][r], acc[mt][t][r]);
     };
 
-    Stage sa, sb;
-    if (g0 < g1) issue(sa, g0);
-    for (int g = g0; g < g1; g += 2) {
-        if (g + 1 < g1) issue(sb, g + 1);
-        compute(sa);
-        if (g + 1 < g1) {
-            if (g + 2 < g1) issue(sa, g + 2);
-            compute(sb);
+    // Software pipeline over this wave's groups.  Iteration g issues x(g+1) into the other
+    // LDS slot, then the packed weights of group g+D-1 into the register stage that has just
+    // been freed (stage index static: the loop is unrolled by D), then consumes group g.  The
+    // pipeline is primed by running the issue part of iterations g0-(D-1) .. g0-1.
+    // The loop body is free of branches: the group count is rounded up to a multiple of D,
+    // loads past the wave's range are clamped to a valid group (they hit data a neighbour
+    // streams anyway) and such groups enter the sum with a step of 0.  Every iteration thus
+    // issues the same number of loads, and since loads complete in issue order "x(g) has
+    // landed" is "at most 2*OW + OX loads are still outstanding" (those issued behind it).
+    constexpr int OW = KSPG * NT + 2 * NT, OX = KSPG * MT;
+    static_assert(XD == 2, "the x ring is double buffered");
+    static_assert(2 * OW + OX < 64, "vmcnt field");
+    static_assert(D >= 3, "x(g) must be issued behind w(g)");
+    auto gc = [&](int g) { return g < groups ? g : groups - 1; };
+    Stage st[D];
+#pragma unroll
+    for (int j = 0; j < D - 1; j++) {
+        if (j == D - 2) issue_x(0, gc(g0));
+        issue_w(st[j], gc(g0 + j));
+    }
+    int xslot = 0;
+    const int nblk = (g1 - g0 + D - 1) / D;
+    for (int b = 0; b < nblk; b++) {
+        const int g = g0 + b * D;
+#pragma unroll
+        for (int d = 0; d < D; d++) {
+            const int gg = g + d;
+            issue_x(xslot ^ 1, gc(gg + 1));
+            issue_w(st[(d + D - 1) % D], gc(gg + D - 1));
+            landed(st[d], std::integral_constant<int, 2 * OW + OX>());
+            compute(st[d], xslot, gg < g1);
+            xslot ^= 1;
         }
     }
+    // Drain the clamped look-ahead loads.  Their destination registers are dead by now as far
+    // as the compiler can tell, but the hardware still writes them when the data arrives: the
+    // empty uses below keep every stage allocated until the wait has completed, so that
+    // nothing else is placed in those registers while a load is in flight.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int j = 0; j < D; j++) {
+#pragma unroll
+        for (int ks = 0; ks < KSPG; ks++)
+#pragma unroll
+            for (int nt = 0; nt < NT; nt++) asm volatile("" ::"v"(st[j].w[ks][nt]));
+#pragma unroll
+        for (int nt = 0; nt < NT; nt++) {
+            asm volatile("" ::"v"(st[j].sc[nt]));
+            asm volatile("" ::"v"(st[j].zr[nt]));
+        }
+    }
+    __syncthreads();  // every wave is done with its x ring before the LDS is reused
 
     // ---- sum the NW waves' K ranges through LDS, in wave order
 #pragma unroll
@@ -249,18 +346,22 @@ w4a16_decode_kernel(int M, int N, int K, const h16 *__restrict__ x, const uint32
             }
         } else {
 #pragma unroll
-            for (int c = 0; c < VW; c++) mypart[(size_t)e * VW + c] = v[c];
+            for (int c = 0; c < VW; c++)
+                __hip_atomic_store(mypart + (size_t)e * VW + c, v[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     if (split == 1) return;
 
-    // ---- cross-workgroup: the last arrival adds the SPLIT partial tiles in split order
-    __threadfence();
+    // ---- cross-workgroup: the last arrival adds the SPLIT partial tiles in split order.
+    // Partials travel as device-scope relaxed atomic stores/loads (written through and read
+    // past the per-XCD L2), so no cache-wide write-back or invalidate is needed: each thread
+    // waits for its own stores to complete, the barrier collects the workgroup, and only then
+    // is the ticket taken.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
-    if (threadIdx.x == 0) ticket_s = atomicAdd(&ws.tickets[tile], 1u);
+    if (threadIdx.x == 0) ticket_s = __hip_atomic_fetch_add(&ws.tickets[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket_s != (unsigned)(split - 1)) return;
-    __threadfence();
     const float *base = ws.partial + (size_t)tile * split * TILE_FLOATS;
     for (int e = threadIdx.x; e < ITEMS; e += NW * 64) {
         const int l = e & 63, r = (e >> 6) & 3, nt = (e >> 8) % NT, mt = (e >> 8) / NT;
@@ -269,7 +370,8 @@ w4a16_decode_kernel(int M, int N, int K, const h16 *__restrict__ x, const uint32
         for (int c = 0; c < VW; c++) v[c] = 0.f;
         for (int s = 0; s < split; s++)
 #pragma unroll
-            for (int c = 0; c < VW; c++) v[c] += __builtin_nontemporal_load(base + (size_t)s * TILE_FLOATS + (size_t)e * VW + c);
+            for (int c = 0; c < VW; c++)
+                v[c] += __hip_atomic_load(base + (size_t)s * TILE_FLOATS + (size_t)e * VW + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int m = mt * 16 + 4 * (l >> 4) + r;
         const int n = n0 + nt * 16 * VW + VW * (l & 15);
         if (m < M && n < N) {
@@ -278,7 +380,8 @@ w4a16_decode_kernel(int M, int N, int K, const h16 *__restrict__ x, const uint32
             for (int c = 0; c < VW; c++) dst[c] = (h16)v[c];
         }
     }
-    if (threadIdx.x == 0) ws.tickets[tile] = 0u;  // ready for the next launch on this stream
+    if (threadIdx.x == 0)  // ready for the next launch on this stream
+        __hip_atomic_store(&ws.tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Any group size that is a multiple of 8 and any M: one thread per output element.
@@ -339,8 +442,8 @@ int get_workspace(Workspace *out, hipStream_t st)
     return SQP_OK;
 }
 
-template <int MT, int VW, int NT, int NW, int KSPG>
-int launch(int M, int N, int K, int split, const h16 *x, const uint32_t *packed, const h16 *scales,
+template <int MT, int VW, int NT, int NW, int KSPG, int D = 3, int XD = 2>
+int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t *packed, const h16 *scales,
            const uint8_t *zeros, h16 *y, hipStream_t st)
 {
     constexpr int BN = 16 * VW * NT;
@@ -354,12 +457,12 @@ int launch(int M, int N, int K, int split, const h16 *x, const uint32_t *packed,
         int rc = get_workspace(&ws, st);
         if (rc) return rc;
     }
-    w4a16_decode_kernel<MT, VW, NT, NW, KSPG><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, x, packed, scales, zeros, y, ws);
+    w4a16_decode_kernel<MT, VW, NT, NW, KSPG, D, XD><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws);
     return sqp_launch_status();
 }
 
 struct Plan {
-    int vw, nw, split;
+    int vw, nt, nw, split;
 };
 
 // Pick strip width, waves per workgroup and K split so that the grid fills 256 compute
@@ -369,6 +472,7 @@ Plan make_plan(int M, int N, int K, int group)
     const int groups = K / group;
     Plan p;
     p.vw = 4;
+    p.nt = 1;
     p.nw = 4;
     p.split = 1;
     const int tiles = (N + 63) / 64;
@@ -384,27 +488,42 @@ Plan make_plan(int M, int N, int K, int group)
     return p;
 }
 
+#define SQP_TRY(VW_, NT_, NW_)                                   \
+    if (p.vw == VW_ && p.nt == NT_ && p.nw == NW_)               \
+        return launch<MT, VW_, NT_, NW_, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
+
 template <int MT, int KSPG>
-int dispatch_mt(const Plan &p, int M, int N, int K, const h16 *x, const uint32_t *packed, const h16 *scales,
+int dispatch_mt(const Plan &p, int M, int N, int K, int cpg, const h16 *x, const uint32_t *packed, const h16 *scales,
                 const uint8_t *zeros, h16 *y, hipStream_t st)
 {
-    return launch<MT, 4, 1, 4, KSPG>(M, N, K, p.split, x, packed, scales, zeros, y, st);
+    if constexpr (KSPG == 4 && MT == 1) {
+        SQP_TRY(4, 1, 2)
+        SQP_TRY(4, 1, 8)
+        SQP_TRY(4, 2, 4)
+    }
+    return launch<MT, 4, 1, 4, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
 }
+#undef SQP_TRY
 
 template <int KSPG>
-int dispatch_kspg(const Plan &p, int M, int N, int K, const h16 *x, const uint32_t *packed, const h16 *scales,
+int dispatch_kspg(const Plan &p, int M, int N, int K, int cpg, const h16 *x, const uint32_t *packed, const h16 *scales,
                   const uint8_t *zeros, h16 *y, hipStream_t st)
 {
-    if (M <= 16) return dispatch_mt<1, KSPG>(p, M, N, K, x, packed, scales, zeros, y, st);
-    if (M <= 32) return dispatch_mt<2, KSPG>(p, M, N, K, x, packed, scales, zeros, y, st);
-    return dispatch_mt<4, KSPG>(p, M, N, K, x, packed, scales, zeros, y, st);
+    if (M <= 16) return dispatch_mt<1, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, st);
+    if (M <= 32) return dispatch_mt<2, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, st);
+    return dispatch_mt<4, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, st);
 }
 
 }  // namespace
 
-// Test/benchmark hook: force the K split (0 = automatic).
+// Test/benchmark hooks: force the K split, or the whole launch plan (0 = automatic).
 static int g_force_split = 0;
+static Plan g_force_plan = {0, 0, 0, 0};
 extern "C" void sqp_debug_set_decode_split(int split) { g_force_split = split; }
+extern "C" void sqp_debug_set_decode_plan(int vw, int nt, int nw, int split)
+{
+    g_force_plan = Plan{vw, nt, nw, split};
+}
 
 int sqp_gemm_generic(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
                      const uint8_t *zeros, h16 *y, hipStream_t stream)
@@ -418,15 +537,14 @@ int sqp_gemm_decode(int M, int N, int K, int group, const h16 *x, const uint32_t
                     const uint8_t *zeros, h16 *y, hipStream_t stream)
 {
     Plan p = make_plan(M, N, K, group);
+    if (g_force_plan.vw > 0) p = g_force_plan;
+    if (p.split > K / group) p.split = K / group;
     if (g_force_split > 0) {
         p.split = g_force_split;
         if (p.split > K / group) p.split = K / group;
     }
-    switch (group) {
-        case 32: return dispatch_kspg<1>(p, M, N, K, x, packed, scales, zeros, y, stream);
-        case 64: return dispatch_kspg<2>(p, M, N, K, x, packed, scales, zeros, y, stream);
-        case 128: return dispatch_kspg<4>(p, M, N, K, x, packed, scales, zeros, y, stream);
-        case 256: return dispatch_kspg<8>(p, M, N, K, x, packed, scales, zeros, y, stream);
-        default: return sqp_gemm_generic(M, N, K, group, x, packed, scales, zeros, y, stream);
-    }
+    if (group == 32) return dispatch_kspg<1>(p, M, N, K, 1, x, packed, scales, zeros, y, stream);
+    if (group == 64) return dispatch_kspg<2>(p, M, N, K, 1, x, packed, scales, zeros, y, stream);
+    if (group % 128 == 0) return dispatch_kspg<4>(p, M, N, K, group / 128, x, packed, scales, zeros, y, stream);
+    return sqp_gemm_generic(M, N, K, group, x, packed, scales, zeros, y, stream);
 }
