@@ -44,15 +44,22 @@ template <> __device__ __forceinline__ uint32_t wzero<1>() { return 0u; }
 template <> __device__ __forceinline__ uint2 wzero<2>() { return make_uint2(0u, 0u); }
 template <> __device__ __forceinline__ uint4 wzero<4>() { return make_uint4(0u, 0u, 0u, 0u); }
 
+// Constants of the nibble unpack, held in registers: v_and_or_b32 cannot take literals.
+struct UnpackConsts {
+    uint32_t mask_lo, mask_hi, magic_lo, magic_hi;
+};
+
 // packed word (8 codes of one column) -> 8 exact fp16 values (code - Z), in the order
 // (k0,k4),(k1,k5),(k2,k6),(k3,k7).  neg_hi = -(1024 + Z), neg_lo = -(64 + Z), both halves.
-__device__ __forceinline__ h16x8 dequant_word(uint32_t w, h16x2 neg_hi, h16x2 neg_lo)
+// 1 shift + 4 and-or + 4 packed adds.
+__device__ __forceinline__ h16x8 dequant_word(uint32_t w, h16x2 neg_hi, h16x2 neg_lo, const UnpackConsts &uc)
 {
     const uint32_t w8 = w >> 8;
-    uint32_t t0 = (w & 0x000f000fu) | 0x64006400u;
-    uint32_t t1 = (w & 0x00f000f0u) | 0x54005400u;
-    uint32_t t2 = (w8 & 0x000f000fu) | 0x64006400u;
-    uint32_t t3 = (w8 & 0x00f000f0u) | 0x54005400u;
+    uint32_t t0, t1, t2, t3;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(t0) : "v"(w), "v"(uc.mask_lo), "v"(uc.magic_lo));
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(t1) : "v"(w), "v"(uc.mask_hi), "v"(uc.magic_hi));
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(t2) : "v"(w8), "v"(uc.mask_lo), "v"(uc.magic_lo));
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(t3) : "v"(w8), "v"(uc.mask_hi), "v"(uc.magic_hi));
     h16x2 b0 = __builtin_bit_cast(h16x2, t0) + neg_hi;
     h16x2 b1 = __builtin_bit_cast(h16x2, t1) + neg_lo;
     h16x2 b2 = __builtin_bit_cast(h16x2, t2) + neg_hi;
@@ -85,7 +92,7 @@ struct Workspace {
 // 128 above 128).  D: register stages of packed weights (groups in flight + 1).
 // XD: LDS stages of activations per wave.
 template <int MT, int VW, int NT, int NW, int KSPG, int D, int XD>
-__global__ void __launch_bounds__(NW * 64)
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MT * NT == 1 ? 3 : 1)))
 w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, const uint32_t *__restrict__ packed,
                     const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y,
                     Workspace ws)
@@ -136,6 +143,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     for (int mt = 0; mt < MT; mt++)
 #pragma unroll
         for (int t = 0; t < NTILE; t++) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const UnpackConsts uc = {0x000f000fu, 0x00f000f0u, 0x64006400u, 0x54005400u};
 
     static_assert(VW == 4, "one dwordx4 of packed words per lane");
     struct Stage {
@@ -147,23 +155,31 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // The weight, step and zero-point loads are written in assembly so that this kernel, not
     // the compiler, decides when to wait for them: the registers of a stage must not be read
     // before the s_waitcnt issued by `landed` below.
+    // Addresses are a scalar base (advanced on the scalar unit) plus a per-lane 32-bit offset
+    // that never changes, so the loads cost no vector arithmetic.
+    const uint32_t voff_w = (uint32_t)(lk * N + 0) * 4u;  // + column, below
+    uint32_t voff_wn[NT], voff_sn[NT], voff_zn[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; nt++) {
+        voff_wn[nt] = voff_w + (uint32_t)ncol[nt] * 4u;
+        voff_sn[nt] = (uint32_t)ncol[nt] * 2u;
+        voff_zn[nt] = (uint32_t)ncol[nt];
+    }
     auto issue_w = [&](Stage &s, int g) {
 #pragma unroll
         for (int ks = 0; ks < KSPG; ks++) {
-            const int row = (g * KSPG + ks) * 4 + lk;  // packed row = k / 8
+            const uint32_t *base = packed + (size_t)(g * KSPG + ks) * 4 * N;  // wave-uniform
 #pragma unroll
-            for (int nt = 0; nt < NT; nt++) {
-                const uint32_t *p = packed + (size_t)row * N + ncol[nt];
-                asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(s.w[ks][nt]) : "v"(p) : "memory");
-            }
+            for (int nt = 0; nt < NT; nt++)
+                asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(s.w[ks][nt]) : "v"(voff_wn[nt]), "s"(base) : "memory");
         }
+        const int gs = g / cpg;  // quantisation group of this chunk
+        const h16 *sbase = scales + (size_t)gs * N;
+        const uint8_t *zbase = zeros + (size_t)gs * N;
 #pragma unroll
         for (int nt = 0; nt < NT; nt++) {
-            const int gs = g / cpg;  // quantisation group of this chunk
-            const h16 *sp = scales + (size_t)gs * N + ncol[nt];
-            const uint8_t *zp = zeros + (size_t)gs * N + ncol[nt];
-            asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(s.sc[nt]) : "v"(sp) : "memory");
-            asm volatile("global_load_dword %0, %1, off" : "=v"(s.zr[nt]) : "v"(zp) : "memory");
+            asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc[nt]) : "v"(voff_sn[nt]), "s"(sbase) : "memory");
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr[nt]) : "v"(voff_zn[nt]), "s"(zbase) : "memory");
         }
     };
     // wait until at most `AFTER` loads are outstanding, then tie the stage's registers to the
@@ -207,11 +223,11 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         for (int nt = 0; nt < NT; nt++)
 #pragma unroll
             for (int c = 0; c < VW; c++) {
-                const int z = (int)((s.zr[nt] >> (8 * c)) & 0xffu);
-                const h16 zh = (h16)(float)z;  // exact
-                const h16 a = (h16)(-1024.0f) - zh, b = (h16)(-64.0f) - zh;
-                neg_hi[nt * VW + c] = h16x2{a, a};
-                neg_lo[nt * VW + c] = h16x2{b, b};
+                // fp16 bit patterns: 1024 + Z is 0x6400 + Z and 64 + Z is 0x5400 + 16 Z (Z <= 15);
+                // with the sign bit, replicated into both halves
+                const uint32_t z = (s.zr[nt] >> (8 * c)) & 0xffu;
+                neg_hi[nt * VW + c] = __builtin_bit_cast(h16x2, z * 0x00010001u + 0xe400e400u);
+                neg_lo[nt * VW + c] = __builtin_bit_cast(h16x2, z * 0x00100010u + 0xd400d400u);
                 const uint32_t sw = s.sc[nt][c >> 1];
                 const h16x2 sv = __builtin_bit_cast(h16x2, sw);
                 delta[nt * VW + c] = live ? (float)((c & 1) ? sv.y : sv.x) : 0.f;
@@ -242,7 +258,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 #pragma unroll
                     for (int c = 0; c < VW; c++) {
                         const int t = nt * VW + c;
-                        const h16x8 b = dequant_word(s.w[ks][nt][c], neg_hi[t], neg_lo[t]);
+                        const h16x8 b = dequant_word(s.w[ks][nt][c], neg_hi[t], neg_lo[t], uc);
 #pragma unroll
                         for (int mt = 0; mt < MT; mt++)
                             accg[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b, accg[mt][t], 0, 0, 0);
