@@ -1,22 +1,30 @@
 // Weight-streaming W4A16 GEMM for small M (decode): y = x * w_hat, Eq. 3 of
 // arXiv 2312.03788 with w_hat = (code - Z) * Delta of Eq. 1, group-wise along K (Sec 2.2).
 //
-// The kernel is bound by the HBM stream of packed weights.  Each wave owns a strip of
-// 16*VW*NT output columns and a contiguous range of quantisation groups along K:
-//   - one dwordx{VW} load per lane fetches, for k-block (lane / 16), the packed words of
-//     VW adjacent columns: a word is 8 consecutive k of one column, which is exactly one
-//     lane's B operand of v_mfma_f32_16x16x32_f16 (column = lane % 16, k-block = lane / 16);
-//   - the codes become exact fp16 integers (code - Z) with 9 VALU ops per word: the
-//     nibbles are OR-ed into the mantissa of 1024.0 (bits 3:0) or 64.0 (bits 7:4) and the
-//     offset (1024 + Z or 64 + Z) is subtracted with a packed fp16 add, which is exact;
-//   - x supplies the A operand (row = lane % 16), permuted to the same nibble order;
-//   - the MFMA accumulates one group in fp32, then the group's step Delta (a per-lane
-//     scalar in the 16x16 accumulator layout: column = lane % 16) scales it into the
-//     running sum: sum_k x (q - Z) Delta = Delta * sum_k x (q - Z).
-// The K ranges of the NW waves of a workgroup are summed through LDS in wave order; with
-// SPLIT > 1 workgroups along K, fp32 partial tiles go to a workspace and the workgroup
-// that arrives last (atomic ticket) adds them in split order, so the result does not
-// depend on scheduling.
+// The kernel is bound by the HBM stream of packed weights, and on this chip that stream is
+// limited by how many cache-line requests a compute unit's vector L1 keeps in flight: the
+// L1 handles requests in order, so every request that is not a weight line (activations,
+// steps, zero points) takes a place a weight line could have had.  The design follows:
+//   - A workgroup of NW waves covers 64*NW output columns; each wave owns a 64-column strip
+//     and every wave walks the same range of K.  One dwordx4 load per lane fetches, for
+//     k-block (lane / 16), the packed words of 4 adjacent columns: a word is 8 consecutive k
+//     of one column, which is exactly one lane's B operand of v_mfma_f32_16x16x32_f16
+//     (column = lane % 16, k-block = lane / 16).
+//   - The activations of a K chunk are fetched ONCE per workgroup, as whole 128-byte lines,
+//     by direct global->LDS loads into a three-slot ring, and every wave takes its A operands
+//     from there (row = lane % 16, permuted to the nibble order of the unpack).
+//   - The codes become exact fp16 integers (code - Z) with 9 VALU ops per word: the nibbles
+//     are OR-ed into the mantissa of 1024.0 (bits 3:0) or 64.0 (bits 7:4) and the offset
+//     (1024 + Z or 64 + Z) is subtracted with a packed fp16 add, which is exact.
+//   - The MFMA accumulates one chunk in fp32, then the step Delta (a per-lane scalar in the
+//     16x16 accumulator layout: column = lane % 16) scales it into the running sum:
+//     sum_k x (q - Z) Delta = Delta * sum_k x (q - Z).
+//   - Weight loads and all waits are written in assembly: two chunks of weights stay in
+//     flight per wave while one is consumed, and the compiler's conservative waits (it cannot
+//     tell ring slots apart) would serialise that.
+// With SPLIT > 1 workgroups along K, fp32 partial tiles go to a workspace and the workgroup
+// that arrives last (atomic ticket) adds them in split order, so the result does not depend
+// on scheduling.
 #include <type_traits>
 
 #include "sqp_common.h"
@@ -25,24 +33,6 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-template <int VW> struct WVec;
-template <> struct WVec<1> { typedef uint32_t T; };
-template <> struct WVec<2> { typedef uint2 T; };
-template <> struct WVec<4> { typedef uint4 T; };
-
-template <int VW> __device__ __forceinline__ uint32_t wword(const typename WVec<VW>::T &v, int c);
-template <> __device__ __forceinline__ uint32_t wword<1>(const uint32_t &v, int) { return v; }
-template <> __device__ __forceinline__ uint32_t wword<2>(const uint2 &v, int c) { return c ? v.y : v.x; }
-template <> __device__ __forceinline__ uint32_t wword<4>(const uint4 &v, int c)
-{
-    return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w));
-}
-
-template <int VW> __device__ __forceinline__ typename WVec<VW>::T wzero();
-template <> __device__ __forceinline__ uint32_t wzero<1>() { return 0u; }
-template <> __device__ __forceinline__ uint2 wzero<2>() { return make_uint2(0u, 0u); }
-template <> __device__ __forceinline__ uint4 wzero<4>() { return make_uint4(0u, 0u, 0u, 0u); }
 
 // Constants of the nibble unpack, held in registers: v_and_or_b32 cannot take literals.
 struct UnpackConsts {
@@ -82,168 +72,172 @@ __device__ __forceinline__ h16x8 permute_x(const u32x4 &v)
 }
 
 struct Workspace {
-    float *partial;      // [tiles][SPLIT][tile floats]
+    float *partial;      // [tiles][SPLIT][NW][REGS][64]
     unsigned *tickets;   // [tiles], zero between launches
 };
 
-// MT: 16-row tiles of x (M <= 16*MT).  VW: packed words per lane per load.  NT: loads per
-// k-step (strip width 16*VW*NT).  NW: waves per workgroup.  KSPG: k-steps (of 32) per
-// chunk; a quantisation group is cpg chunks (cpg = 1 unless the group is a multiple of
-// 128 above 128).  D: register stages of packed weights (groups in flight + 1).
-// XD: LDS stages of activations per wave.
-template <int MT, int VW, int NT, int NW, int KSPG, int D, int XD>
-__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MT * NT == 1 ? 3 : 1)))
+// MT: 16-row tiles of x (M <= 16*MT).  NW: waves (64-column strips) per workgroup.
+// KSPG: k-steps (of 32) per chunk; a quantisation group is cpg chunks (cpg = 1 unless the
+// group is a multiple of 128 above 128).
+template <int MT, int NW, int KSPG>
+__global__ void __launch_bounds__(NW * 64)
 w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, const uint32_t *__restrict__ packed,
                     const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y,
                     Workspace ws)
 {
-    typedef typename WVec<VW>::T wvec;
-    constexpr int NTILE = NT * VW;        // 16x16 accumulator tiles per m-tile
-    constexpr int REGS = MT * NTILE * 4;  // fp32 accumulator registers per lane
-    constexpr int BN = 16 * VW * NT;      // strip width
-    // Activations reach the matrix cores through a per-wave LDS ring filled by direct
-    // global->LDS loads (no registers held while they are in flight); the same LDS is
-    // reused for the cross-wave sum at the end.
-    constexpr int XSTAGE = KSPG * MT * 1024;  // bytes: one group of x for this wave
-    constexpr int XRING = XD * XSTAGE;
-    constexpr int RED_BYTES = NW * REGS * 64 * 4;
-    constexpr int SMEM = NW * XRING > RED_BYTES ? NW * XRING : RED_BYTES;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+    constexpr int D = 3;                   // register stages of packed weights
+    constexpr int XD = 3;                  // LDS slots of activations
+    constexpr int REGS = MT * 4 * 4;       // fp32 accumulator registers per lane
+    constexpr int BN = 64 * NW;
+    // One chunk of x in LDS: MT*16 rows of KSPG*64 bytes, stored as 1 KB blocks, one per
+    // direct load instruction: a block holds 16/KSPG rows, PP = 4*KSPG 16-byte pieces each.
+    constexpr int PP = 4 * KSPG;
+    constexpr int RPB = 16 / KSPG;         // rows per block
+    constexpr int XBLOCKS = MT * KSPG;     // blocks per chunk
+    constexpr int XSTAGE = XBLOCKS * 1024;
+    constexpr int OX = (XBLOCKS + NW - 1) / NW;  // direct loads per wave per chunk
+    constexpr int OW = KSPG + 2;                 // weight-side loads per wave per chunk
+    static_assert(OX + OW < 64, "vmcnt field");
+    __shared__ __attribute__((aligned(1024))) unsigned char xring[XD * XSTAGE];
     __shared__ unsigned ticket_s;
-    float(*red)[REGS][64] = reinterpret_cast<float(*)[REGS][64]>(smem);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept scalar
     const int lc = lane & 15, lk = lane >> 4;
-    const int n0 = blockIdx.x * BN;
+    const int tile = blockIdx.x;
+    const int n0 = tile * BN + wave * 64;
     const int split = gridDim.y, sidx = blockIdx.y;
-    const int groups = K / (32 * KSPG);
-    // this workgroup's group range, then this wave's share of it
-    const int gb0 = (int)((long)groups * sidx / split), gb1 = (int)((long)groups * (sidx + 1) / split);
-    const int g0 = gb0 + (gb1 - gb0) * wave / NW, g1 = gb0 + (gb1 - gb0) * (wave + 1) / NW;
-    unsigned char *xring = smem + wave * XRING;
+    const int chunks = K / (32 * KSPG);
+    // this workgroup's chunk range (all waves walk it together)
+    const int g0 = (int)((long)chunks * sidx / split), g1 = (int)((long)chunks * (sidx + 1) / split);
 
     // lanes past the last column read column 0 instead; their results are never stored
-    int ncol[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; nt++) {
-        ncol[nt] = n0 + nt * 16 * VW + VW * lc;
-        if (ncol[nt] >= N) ncol[nt] = 0;
-    }
-    const h16 *xsrc[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        int m = mt * 16 + lc;
-        m = m < M ? m : M - 1;
-        xsrc[mt] = x + (size_t)m * K + lk * 8;
-    }
+    int ncol = n0 + 4 * lc;
+    if (ncol >= N) ncol = 0;
 
-    f32x4 acc[MT][NTILE];
+    f32x4 acc[MT][4];
 #pragma unroll
     for (int mt = 0; mt < MT; mt++)
 #pragma unroll
-        for (int t = 0; t < NTILE; t++) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < 4; t++) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     const UnpackConsts uc = {0x000f000fu, 0x00f000f0u, 0x64006400u, 0x54005400u};
 
-    static_assert(VW == 4, "one dwordx4 of packed words per lane");
     struct Stage {
-        u32x4 w[KSPG][NT];
-        u32x2 sc[NT];     // 4 fp16 steps
-        uint32_t zr[NT];  // 4 zero points, one byte each
+        u32x4 w[KSPG];
+        u32x2 sc;     // 4 fp16 steps
+        uint32_t zr;  // 4 zero points, one byte each
     };
 
-    // The weight, step and zero-point loads are written in assembly so that this kernel, not
-    // the compiler, decides when to wait for them: the registers of a stage must not be read
-    // before the s_waitcnt issued by `landed` below.
-    // Addresses are a scalar base (advanced on the scalar unit) plus a per-lane 32-bit offset
-    // that never changes, so the loads cost no vector arithmetic.
-    const uint32_t voff_w = (uint32_t)(lk * N + 0) * 4u;  // + column, below
-    uint32_t voff_wn[NT], voff_sn[NT], voff_zn[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; nt++) {
-        voff_wn[nt] = voff_w + (uint32_t)ncol[nt] * 4u;
-        voff_sn[nt] = (uint32_t)ncol[nt] * 2u;
-        voff_zn[nt] = (uint32_t)ncol[nt];
-    }
+    // Weight-side addresses are a scalar base (advanced on the scalar unit) plus a per-lane
+    // 32-bit offset that never changes, so the loads cost no vector arithmetic.  The loads are
+    // written in assembly so that this kernel, not the compiler, decides when to wait for
+    // them: a stage must not be read before `landed` below.
+#ifdef SQP_PROBE_TILED
+    const uint32_t voff_w = (uint32_t)(lk * 64 + (ncol & 63)) * 4u + (uint32_t)(ncol >> 6) * (uint32_t)(K / 8) * 256u;
+    const int wrow_stride = 64;
+#else
+    const uint32_t voff_w = (uint32_t)(lk * N + ncol) * 4u;
+    const int wrow_stride = N;
+#endif
+    const uint32_t voff_s = (uint32_t)ncol * 2u, voff_z = (uint32_t)ncol;
     auto issue_w = [&](Stage &s, int g) {
 #pragma unroll
         for (int ks = 0; ks < KSPG; ks++) {
-            const uint32_t *base = packed + (size_t)(g * KSPG + ks) * 4 * N;  // wave-uniform
-#pragma unroll
-            for (int nt = 0; nt < NT; nt++)
-                asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(s.w[ks][nt]) : "v"(voff_wn[nt]), "s"(base) : "memory");
+            const uint32_t *base = packed + (size_t)(g * KSPG + ks) * 4 * wrow_stride;  // wave-uniform
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
         }
         const int gs = g / cpg;  // quantisation group of this chunk
         const h16 *sbase = scales + (size_t)gs * N;
         const uint8_t *zbase = zeros + (size_t)gs * N;
-#pragma unroll
-        for (int nt = 0; nt < NT; nt++) {
-            asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc[nt]) : "v"(voff_sn[nt]), "s"(sbase) : "memory");
-            asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr[nt]) : "v"(voff_zn[nt]), "s"(zbase) : "memory");
-        }
+        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sbase) : "memory");
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zbase) : "memory");
     };
-    // wait until at most `AFTER` loads are outstanding, then tie the stage's registers to the
+    // wait until at most `after` loads are outstanding, then tie the stage's registers to the
     // wait so that no use of them is scheduled ahead of it
     auto landed = [&](Stage &s, auto after) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(after)::value) : "memory");
 #pragma unroll
-        for (int ks = 0; ks < KSPG; ks++)
+        for (int ks = 0; ks < KSPG; ks++) asm volatile("" : "+v"(s.w[ks]));
+        asm volatile("" : "+v"(s.sc));
+        asm volatile("" : "+v"(s.zr));
+    };
+
+    // Activations: wave w copies blocks w, w+NW, ... of the chunk straight into LDS.  Lane i
+    // of a block handles row i / PP of the block and fetches piece (i % PP) ^ (row % PP) of
+    // that row, so that a row's pieces (whole 128-byte lines) come from adjacent lanes, while
+    // in LDS (where the hardware puts lane i at byte 16*i of the block) the pieces the 16
+    // rows need for one k-step fall into 16 different bank groups.
+    const int xrr = lane / PP, xpp = lane % PP;
+    uint32_t xoff[OX];  // per-lane byte offset into x of each block this wave copies
 #pragma unroll
-            for (int nt = 0; nt < NT; nt++) asm volatile("" : "+v"(s.w[ks][nt]));
+    for (int i = 0; i < OX; i++) {
+        const int b = (wave + i * NW) % XBLOCKS;
+        const int row = b * RPB + xrr;
+        const int rowc = row < M ? row : M - 1;
+        xoff[i] = (uint32_t)rowc * (uint32_t)K * 2u + (uint32_t)((xpp ^ (row % PP)) * 16);
+    }
+    auto issue_x = [&](int slot, int g) {
+        const h16 *base = x + (size_t)g * (32 * KSPG);  // wave-uniform
 #pragma unroll
-        for (int nt = 0; nt < NT; nt++) {
-            asm volatile("" : "+v"(s.sc[nt]));
-            asm volatile("" : "+v"(s.zr[nt]));
+        for (int i = 0; i < OX; i++) {
+            const int b = (wave + i * NW) % XBLOCKS;
+            const unsigned char *src = reinterpret_cast<const unsigned char *>(base) + xoff[i];
+            unsigned char *dst = xring + slot * XSTAGE + b * 1024;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
         }
     };
-
-    // lane (row lc, k-block lk) copies its 16 bytes of x straight into LDS; the hardware
-    // places lane i at byte 16*i of the destination block, which is where it reads them back.
-    auto issue_x = [&](int slot, int g) {
+    // LDS byte address of this lane's A fragment (row lc of m-tile mt) in slot 0, piece 0
+    uint32_t xrd[MT];
 #pragma unroll
-        for (int ks = 0; ks < KSPG; ks++)
-#pragma unroll
-            for (int mt = 0; mt < MT; mt++) {
-                const h16 *src = xsrc[mt] + (size_t)(g * KSPG + ks) * 32;
-                unsigned char *dst = xring + slot * XSTAGE + (ks * MT + mt) * 1024;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                 (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-            }
-    };
+    for (int mt = 0; mt < MT; mt++) {
+        const int row = mt * 16 + lc;
+        xrd[mt] = (uint32_t)(size_t)xring + (uint32_t)((row / RPB) * 1024 + (row % RPB) * PP * 16);
+    }
+    const int xsw = lc % PP;  // the row's swizzle (16 % PP == 0, so mt does not matter)
 
     auto compute = [&](const Stage &s, int slot, bool live) {
-        f32x4 accg[MT][NTILE];
+#ifdef SQP_PROBE_NOCOMPUTE
+        {
+            uint32_t h = s.zr ^ s.sc[0] ^ s.sc[1];
+#pragma unroll
+            for (int ks = 0; ks < KSPG; ks++) h ^= s.w[ks][0] ^ s.w[ks][1] ^ s.w[ks][2] ^ s.w[ks][3];
+            acc[0][0][0] += live ? __builtin_bit_cast(float, h & 0x3fffffffu) : 0.f;
+            (void)slot;
+            return;
+        }
+#endif
+        f32x4 accg[MT][4];
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
 #pragma unroll
-            for (int t = 0; t < NTILE; t++) accg[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-        h16x2 neg_hi[NTILE], neg_lo[NTILE];
-        float delta[NTILE];
+            for (int t = 0; t < 4; t++) accg[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        h16x2 neg_hi[4], neg_lo[4];
+        float delta[4];
 #pragma unroll
-        for (int nt = 0; nt < NT; nt++)
-#pragma unroll
-            for (int c = 0; c < VW; c++) {
-                // fp16 bit patterns: 1024 + Z is 0x6400 + Z and 64 + Z is 0x5400 + 16 Z (Z <= 15);
-                // with the sign bit, replicated into both halves
-                const uint32_t z = (s.zr[nt] >> (8 * c)) & 0xffu;
-                neg_hi[nt * VW + c] = __builtin_bit_cast(h16x2, z * 0x00010001u + 0xe400e400u);
-                neg_lo[nt * VW + c] = __builtin_bit_cast(h16x2, z * 0x00100010u + 0xd400d400u);
-                const uint32_t sw = s.sc[nt][c >> 1];
-                const h16x2 sv = __builtin_bit_cast(h16x2, sw);
-                delta[nt * VW + c] = live ? (float)((c & 1) ? sv.y : sv.x) : 0.f;
-            }
-        // The x fragments of the whole group come out of the LDS ring in one go.  The reads
-        // are written in assembly because the compiler cannot tell which ring slot a direct
-        // global->LDS load filled and would otherwise wait for every outstanding load; the
-        // caller has already waited for exactly the loads that filled this slot.
-        const unsigned xs = (unsigned)(size_t)(xring + slot * XSTAGE + lane * 16);
+        for (int c = 0; c < 4; c++) {
+            // fp16 bit patterns: 1024 + Z is 0x6400 + Z and 64 + Z is 0x5400 + 16 Z (Z <= 15);
+            // with the sign bit, replicated into both halves
+            const uint32_t z = (s.zr >> (8 * c)) & 0xffu;
+            neg_hi[c] = __builtin_bit_cast(h16x2, z * 0x00010001u + 0xe400e400u);
+            neg_lo[c] = __builtin_bit_cast(h16x2, z * 0x00100010u + 0xd400d400u);
+            const h16x2 sv = __builtin_bit_cast(h16x2, (uint32_t)s.sc[c >> 1]);
+            delta[c] = live ? (float)((c & 1) ? sv.y : sv.x) : 0.f;
+        }
+        // The A fragments come out of the LDS ring with reads written in assembly: the
+        // compiler cannot tell which ring slot a direct global->LDS load filled and would wait
+        // for every outstanding load; the caller has already waited for this slot.
         constexpr int XB = MT == 1 ? KSPG : 1;  // k-steps fetched from LDS per batch
 #pragma unroll
         for (int kb = 0; kb < KSPG; kb += XB) {
             u32x4 xa[XB * MT];
 #pragma unroll
-            for (int i = 0; i < XB * MT; i++)
-                asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(xa[i]) : "v"(xs), "n"((kb * MT + i) * 1024) : "memory");
+            for (int kk = 0; kk < XB; kk++)
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++) {
+                    const uint32_t a = xrd[mt] + (uint32_t)(slot * XSTAGE) + (uint32_t)((((kb + kk) * 4 + lk) ^ xsw) * 16);
+                    asm volatile("ds_read_b128 %0, %1" : "=&v"(xa[kk * MT + mt]) : "v"(a) : "memory");
+                }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
             for (int i = 0; i < XB * MT; i++) asm volatile("" : "+v"(xa[i]));  // no use ahead of the wait
@@ -254,57 +248,52 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 #pragma unroll
                 for (int mt = 0; mt < MT; mt++) a[mt] = permute_x(xa[kk * MT + mt]);
 #pragma unroll
-                for (int nt = 0; nt < NT; nt++)
+                for (int c = 0; c < 4; c++) {
+                    const h16x8 b = dequant_word(s.w[ks][c], neg_hi[c], neg_lo[c], uc);
 #pragma unroll
-                    for (int c = 0; c < VW; c++) {
-                        const int t = nt * VW + c;
-                        const h16x8 b = dequant_word(s.w[ks][nt][c], neg_hi[t], neg_lo[t], uc);
-#pragma unroll
-                        for (int mt = 0; mt < MT; mt++)
-                            accg[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b, accg[mt][t], 0, 0, 0);
-                    }
+                    for (int mt = 0; mt < MT; mt++)
+                        accg[mt][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b, accg[mt][c], 0, 0, 0);
+                }
             }
         }
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
 #pragma unroll
-            for (int t = 0; t < NTILE; t++)
+            for (int t = 0; t < 4; t++)
 #pragma unroll
                 for (int r = 0; r < 4; r++) acc[mt][t][r] = fmaf(delta[t], accg[mt][t][r], acc[mt][t][r]);
     };
 
-    // Software pipeline over this wave's groups.  Iteration g issues x(g+1) into the other
-    // LDS slot, then the packed weights of group g+D-1 into the register stage that has just
-    // been freed (stage index static: the loop is unrolled by D), then consumes group g.  The
-    // pipeline is primed by running the issue part of iterations g0-(D-1) .. g0-1.
-    // The loop body is free of branches: the group count is rounded up to a multiple of D,
-    // loads past the wave's range are clamped to a valid group (they hit data a neighbour
-    // streams anyway) and such groups enter the sum with a step of 0.  Every iteration thus
-    // issues the same number of loads, and since loads complete in issue order "x(g) has
-    // landed" is "at most 2*OW + OX loads are still outstanding" (those issued behind it).
-    constexpr int OW = KSPG * NT + 2 * NT, OX = KSPG * MT;
-    static_assert(XD == 2, "the x ring is double buffered");
-    static_assert(2 * OW + OX < 64, "vmcnt field");
-    static_assert(D >= 3, "x(g) must be issued behind w(g)");
-    auto gc = [&](int g) { return g < groups ? g : groups - 1; };
+    // Software pipeline over the chunk range.  Iteration g: wait for everything issued up to
+    // iteration g-2 (weights and this wave's part of x of chunk g), meet the other waves (now
+    // all of x(g) is in LDS and nobody reads slot (g+2) % 3 any more), issue x(g+2) and the
+    // weights of chunk g+2 into the stage just freed (stage index static: the loop is unrolled
+    // by D), consume chunk g.  The pipeline is primed by issuing chunks g0 and g0+1.
+    // The loop body is free of branches: the chunk count is rounded up to a multiple of D,
+    // loads past the range are clamped to a valid chunk (they hit data a neighbour streams
+    // anyway) and such chunks enter the sum with a step of 0.  Every iteration thus issues the
+    // same OX + OW loads, and since loads complete in issue order "at most OX + OW loads
+    // outstanding" means all but the previous iteration's have landed.
+    auto gc = [&](int g) { return g < chunks ? g : chunks - 1; };
     Stage st[D];
-#pragma unroll
-    for (int j = 0; j < D - 1; j++) {
-        if (j == D - 2) issue_x(0, gc(g0));
-        issue_w(st[j], gc(g0 + j));
-    }
-    int xslot = 0;
+    issue_x(0, gc(g0));
+    issue_w(st[0], gc(g0));
+    issue_x(1, gc(g0 + 1));
+    issue_w(st[1], gc(g0 + 1));
+    int slot = 0;  // ring slot of chunk g
     const int nblk = (g1 - g0 + D - 1) / D;
     for (int b = 0; b < nblk; b++) {
         const int g = g0 + b * D;
 #pragma unroll
         for (int d = 0; d < D; d++) {
             const int gg = g + d;
-            issue_x(xslot ^ 1, gc(gg + 1));
-            issue_w(st[(d + D - 1) % D], gc(gg + D - 1));
-            landed(st[d], std::integral_constant<int, 2 * OW + OX>());
-            compute(st[d], xslot, gg < g1);
-            xslot ^= 1;
+            landed(st[d], std::integral_constant<int, OX + OW>());
+            asm volatile("s_barrier" ::: "memory");
+            const int fill = slot >= 1 ? slot - 1 : XD - 1;  // (slot + 2) % 3
+            issue_x(fill, gc(gg + 2));
+            issue_w(st[(d + 2) % D], gc(gg + 2));
+            compute(st[d], slot, gg < g1);
+            slot = slot + 1 == XD ? 0 : slot + 1;
         }
     }
     // Drain the clamped look-ahead loads.  Their destination registers are dead by now as far
@@ -315,86 +304,69 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 #pragma unroll
     for (int j = 0; j < D; j++) {
 #pragma unroll
-        for (int ks = 0; ks < KSPG; ks++)
-#pragma unroll
-            for (int nt = 0; nt < NT; nt++) asm volatile("" ::"v"(st[j].w[ks][nt]));
-#pragma unroll
-        for (int nt = 0; nt < NT; nt++) {
-            asm volatile("" ::"v"(st[j].sc[nt]));
-            asm volatile("" ::"v"(st[j].zr[nt]));
-        }
+        for (int ks = 0; ks < KSPG; ks++) asm volatile("" ::"v"(st[j].w[ks]));
+        asm volatile("" ::"v"(st[j].sc));
+        asm volatile("" ::"v"(st[j].zr));
     }
-    __syncthreads();  // every wave is done with its x ring before the LDS is reused
 
-    // ---- sum the NW waves' K ranges through LDS, in wave order
+    // ---- epilogue.  Accumulator tile t, register r of a lane: row mt*16 + 4*(lane/16) + r,
+    // column n0 + 4*(lane%16) + t.
+    const int nout = n0 + 4 * lc;
+    if (split == 1) {
+        if (nout < N) {
 #pragma unroll
-    for (int mt = 0; mt < MT; mt++)
+            for (int mt = 0; mt < MT; mt++)
 #pragma unroll
-        for (int t = 0; t < NTILE; t++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) red[wave][(mt * NTILE + t) * 4 + r][lane] = acc[mt][t][r];
-    __syncthreads();
-
-    // output item e = (mt, nt, r, lane): VW adjacent columns of one row
-    constexpr int ITEMS = MT * NT * 4 * 64;
-    constexpr int TILE_FLOATS = ITEMS * VW;
-    const int tile = blockIdx.x;
-    float *mypart = ws.partial ? ws.partial + ((size_t)tile * split + sidx) * TILE_FLOATS : nullptr;
-
-    for (int e = threadIdx.x; e < ITEMS; e += NW * 64) {
-        const int l = e & 63, r = (e >> 6) & 3, nt = (e >> 8) % NT, mt = (e >> 8) / NT;
-        float v[VW];
-#pragma unroll
-        for (int c = 0; c < VW; c++) {
-            const int reg = (mt * NTILE + nt * VW + c) * 4 + r;
-            float sum = red[0][reg][l];
-#pragma unroll
-            for (int w = 1; w < NW; w++) sum += red[w][reg][l];
-            v[c] = sum;
+                for (int r = 0; r < 4; r++) {
+                    const int m = mt * 16 + 4 * lk + r;
+                    if (m < M) {
+                        h16x4 o;
+                        o.x = (h16)acc[mt][0][r]; o.y = (h16)acc[mt][1][r];
+                        o.z = (h16)acc[mt][2][r]; o.w = (h16)acc[mt][3][r];
+                        *reinterpret_cast<h16x4 *>(y + (size_t)m * N + nout) = o;
+                    }
+                }
         }
-        if (split == 1) {
-            const int m = mt * 16 + 4 * (l >> 4) + r;
-            const int n = n0 + nt * 16 * VW + VW * (l & 15);
-            if (m < M && n < N) {
-                h16 *dst = y + (size_t)m * N + n;
-#pragma unroll
-                for (int c = 0; c < VW; c++) dst[c] = (h16)v[c];
-            }
-        } else {
-#pragma unroll
-            for (int c = 0; c < VW; c++)
-                __hip_atomic_store(mypart + (size_t)e * VW + c, v[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        return;
     }
-    if (split == 1) return;
 
     // ---- cross-workgroup: the last arrival adds the SPLIT partial tiles in split order.
     // Partials travel as device-scope relaxed atomic stores/loads (written through and read
     // past the per-XCD L2), so no cache-wide write-back or invalidate is needed: each thread
     // waits for its own stores to complete, the barrier collects the workgroup, and only then
     // is the ticket taken.
+    float *mine = ws.partial + (((size_t)tile * split + sidx) * NW + wave) * (REGS * 64) + lane;
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int t = 0; t < 4; t++)
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                __hip_atomic_store(mine + ((mt * 4 + t) * 4 + r) * 64, acc[mt][t][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (threadIdx.x == 0) ticket_s = __hip_atomic_fetch_add(&ws.tickets[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket_s != (unsigned)(split - 1)) return;
-    const float *base = ws.partial + (size_t)tile * split * TILE_FLOATS;
-    for (int e = threadIdx.x; e < ITEMS; e += NW * 64) {
-        const int l = e & 63, r = (e >> 6) & 3, nt = (e >> 8) % NT, mt = (e >> 8) / NT;
-        float v[VW];
+    if (nout < N) {
+        const float *base = ws.partial + (((size_t)tile * split) * NW + wave) * (REGS * 64) + lane;
 #pragma unroll
-        for (int c = 0; c < VW; c++) v[c] = 0.f;
-        for (int s = 0; s < split; s++)
+        for (int mt = 0; mt < MT; mt++)
 #pragma unroll
-            for (int c = 0; c < VW; c++)
-                v[c] += __hip_atomic_load(base + (size_t)s * TILE_FLOATS + (size_t)e * VW + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int m = mt * 16 + 4 * (l >> 4) + r;
-        const int n = n0 + nt * 16 * VW + VW * (l & 15);
-        if (m < M && n < N) {
-            h16 *dst = y + (size_t)m * N + n;
+            for (int r = 0; r < 4; r++) {
+                float v[4] = {0.f, 0.f, 0.f, 0.f};
+                for (int s = 0; s < split; s++)
 #pragma unroll
-            for (int c = 0; c < VW; c++) dst[c] = (h16)v[c];
-        }
+                    for (int t = 0; t < 4; t++)
+                        v[t] += __hip_atomic_load(base + (size_t)s * NW * (REGS * 64) + ((mt * 4 + t) * 4 + r) * 64,
+                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int m = mt * 16 + 4 * lk + r;
+                if (m < M) {
+                    h16x4 o;
+                    o.x = (h16)v[0]; o.y = (h16)v[1]; o.z = (h16)v[2]; o.w = (h16)v[3];
+                    *reinterpret_cast<h16x4 *>(y + (size_t)m * N + nout) = o;
+                }
+            }
     }
     if (threadIdx.x == 0)  // ready for the next launch on this stream
         __hip_atomic_store(&ws.tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -458,68 +430,62 @@ int get_workspace(Workspace *out, hipStream_t st)
     return SQP_OK;
 }
 
-template <int MT, int VW, int NT, int NW, int KSPG, int D = 3, int XD = 2>
+template <int MT, int NW, int KSPG>
 int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t *packed, const h16 *scales,
            const uint8_t *zeros, h16 *y, hipStream_t st)
 {
-    constexpr int BN = 16 * VW * NT;
+    constexpr int BN = 64 * NW;
     const int tiles = (N + BN - 1) / BN;
+    const int chunks = K / (32 * KSPG);
+    if (split > chunks) split = chunks;
+    if (split < 1) split = 1;
     Workspace ws = {nullptr, nullptr};
     if (split > 1) {
-        const size_t tile_bytes = (size_t)MT * NT * 4 * 64 * VW * sizeof(float);
+        const size_t tile_bytes = (size_t)NW * MT * 16 * 64 * sizeof(float);
         if (tiles > WS_TICKETS || (size_t)tiles * split * tile_bytes > WS_PARTIAL_BYTES) split = 1;
     }
     if (split > 1) {
         int rc = get_workspace(&ws, st);
         if (rc) return rc;
     }
-    w4a16_decode_kernel<MT, VW, NT, NW, KSPG, D, XD><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws);
+    w4a16_decode_kernel<MT, NW, KSPG><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws);
     return sqp_launch_status();
 }
 
 struct Plan {
-    int vw, nt, nw, split;
+    int nw, split;
 };
 
-// Pick strip width, waves per workgroup and K split so that the grid fills 256 compute
-// units several times over while every wave still streams a few groups.
-Plan make_plan(int M, int N, int K, int group)
+// Strips per workgroup and K split, from sweeps on Code Llama shapes: about a thousand waves
+// in flight keep the memory system busy; beyond that the fp32 partial tiles of the K split
+// cost more than the extra parallelism brings.  Very wide layers take two strips per
+// workgroup (more, smaller workgroups balance better over 256 compute units).
+Plan make_plan(int M, int N, int K, int chunk)
 {
-    const int groups = K / group;
+    const int chunks = K / chunk;
     Plan p;
-    p.vw = 4;
-    p.nt = 1;
-    p.nw = 4;
-    p.split = 1;
-    const int tiles = (N + 63) / 64;
-    // target about 8 waves per compute unit in flight
-    int want = (2048 + tiles * p.nw - 1) / (tiles * p.nw);
-    int max_split = groups / (p.nw * 2);
+    p.nw = N >= 32768 ? 2 : 4;
+    const int tiles = (N + 64 * p.nw - 1) / (64 * p.nw);
+    const int target_waves = p.nw == 2 ? 1400 : 1000;
+    int want = (target_waves + tiles * p.nw / 2) / (tiles * p.nw);
+    int max_split = chunks / 4;  // at least four chunks per workgroup
     if (max_split < 1) max_split = 1;
     if (want > max_split) want = max_split;
-    if (want > 16) want = 16;
     if (want < 1) want = 1;
     p.split = want;
     (void)M;
     return p;
 }
 
-#define SQP_TRY(VW_, NT_, NW_)                                   \
-    if (p.vw == VW_ && p.nt == NT_ && p.nw == NW_)               \
-        return launch<MT, VW_, NT_, NW_, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
-
 template <int MT, int KSPG>
 int dispatch_mt(const Plan &p, int M, int N, int K, int cpg, const h16 *x, const uint32_t *packed, const h16 *scales,
                 const uint8_t *zeros, h16 *y, hipStream_t st)
 {
-    if constexpr (KSPG == 4 && MT == 1) {
-        SQP_TRY(4, 1, 2)
-        SQP_TRY(4, 1, 8)
-        SQP_TRY(4, 2, 4)
-    }
-    return launch<MT, 4, 1, 4, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
+    if (p.nw == 2) return launch<MT, 2, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
+    if constexpr (MT < 4)  // eight waves of the 64-row variant would not fit the register file
+        if (p.nw == 8) return launch<MT, 8, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
+    return launch<MT, 4, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
 }
-#undef SQP_TRY
 
 template <int KSPG>
 int dispatch_kspg(const Plan &p, int M, int N, int K, int cpg, const h16 *x, const uint32_t *packed, const h16 *scales,
@@ -534,12 +500,9 @@ int dispatch_kspg(const Plan &p, int M, int N, int K, int cpg, const h16 *x, con
 
 // Test/benchmark hooks: force the K split, or the whole launch plan (0 = automatic).
 static int g_force_split = 0;
-static Plan g_force_plan = {0, 0, 0, 0};
+static Plan g_force_plan = {0, 0};
 extern "C" void sqp_debug_set_decode_split(int split) { g_force_split = split; }
-extern "C" void sqp_debug_set_decode_plan(int vw, int nt, int nw, int split)
-{
-    g_force_plan = Plan{vw, nt, nw, split};
-}
+extern "C" void sqp_debug_set_decode_plan(int nw, int split) { g_force_plan = Plan{nw, split}; }
 
 int sqp_gemm_generic(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
                      const uint8_t *zeros, h16 *y, hipStream_t stream)
@@ -552,13 +515,10 @@ int sqp_gemm_generic(int M, int N, int K, int group, const h16 *x, const uint32_
 int sqp_gemm_decode(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
                     const uint8_t *zeros, h16 *y, hipStream_t stream)
 {
-    Plan p = make_plan(M, N, K, group);
-    if (g_force_plan.vw > 0) p = g_force_plan;
-    if (p.split > K / group) p.split = K / group;
-    if (g_force_split > 0) {
-        p.split = g_force_split;
-        if (p.split > K / group) p.split = K / group;
-    }
+    const int chunk = group % 128 == 0 ? 128 : group;
+    Plan p = make_plan(M, N, K, chunk);
+    if (g_force_plan.nw > 0) p = g_force_plan;
+    if (g_force_split > 0) p.split = g_force_split;
     if (group == 32) return dispatch_kspg<1>(p, M, N, K, 1, x, packed, scales, zeros, y, stream);
     if (group == 64) return dispatch_kspg<2>(p, M, N, K, 1, x, packed, scales, zeros, y, stream);
     if (group % 128 == 0) return dispatch_kspg<4>(p, M, N, K, group / 128, x, packed, scales, zeros, y, stream);
