@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A16 linear-layer hot path on one MI355X.
+
+One step = one pass of the quantised linear layers (Eq. 3 of arXiv 2312.03788) of a whole
+Code Llama-34B-shaped decoder stack at decode batch M=16: 48 layers x 4 merged linears
+(8192->10240, 8192->8192, 8192->44032, 22016->8192), every layer with its own packed
+int4 weights (17.3 GB resident in HBM, so each GEMM streams from HBM, not from cache).
+The weights are produced on the GPU by the library's own smoothing + quantise/pack
+kernels from seeded synthetic fp16 weights (N(0, 0.02)) and activations with 1 % outlier
+channels (x50); the timed region contains only sqp_w4a16_gemm launches.
+
+Prints ONE JSON line: whole-job GB/s of algorithmic bytes (4-bit codes + fp16 step +
+4-bit zero point per group + fp16 X and Y), a `roofline` object for the decode kernel and a
+`cpu_baseline` object (the CPU oracle timed on a bounded sample of the same workload).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2516.6
+
+# HBM bytes per decode launch (averaged over the four shapes of the sweep) from the
+# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (None until measured).
+TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--model", default="34b", choices=["7b", "13b", "34b"])
+    ap.add_argument("--m", type=int, default=16, help="decode rows")
+    ap.add_argument("--layers", type=int, default=0, help="0 = the model's layer count")
+    ap.add_argument("--no-graph", action="store_true", help="launch from Python instead of replaying a HIP graph")
+    ap.add_argument("--no-extra", action="store_true", help="skip the M=1 / prefill / companion side measurements")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2312_03788_amd as sqp
+    import workloads as wl
+
+    sqp.lib()  # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    shapes = wl.MODEL_SHAPES[args.model]
+    nlayers = args.layers or wl.MODEL_LAYERS[args.model]
+    M = args.m
+    G = wl.GROUP
+
+    # ---- resident quantised model, built with the library's own kernels
+    gen = torch.Generator(device=dev)
+    outl = {K: torch.from_numpy(wl.outlier_channels(K)).to(dev) for K, _ in shapes}
+
+    def activation(m, K, seed):
+        gen.manual_seed(seed)
+        x = torch.randn((m, K), device=dev, generator=gen, dtype=torch.float32)
+        x[:, outl[K]] *= 50.0
+        return x.half()
+
+    t_build = time.time()
+    layers = []      # per layer: list of (packed, scales, zeros)
+    s_first = {}     # smoothing factors of layer 0, per shape (for the activations)
+    for layer in range(nlayers):
+        per = []
+        for si, (K, N) in enumerate(shapes):
+            gen.manual_seed(1000 + 16 * layer + si)
+            w = (torch.randn((K, N), device=dev, generator=gen, dtype=torch.float32) * 0.02).half()
+            xcal = activation(wl.T_CAL, K, 3000)
+            s = sqp.smooth_scales(xcal, w, wl.ALPHA)
+            sqp.smooth_apply_w(w, s, out=w)
+            per.append(sqp.quantize_pack(w, G))
+            if layer == 0:
+                s_first[si] = s
+            del w, xcal
+        layers.append(per)
+    xs = []
+    for si, (K, N) in enumerate(shapes):
+        xs.append(sqp.smooth_apply_x(activation(M, K, 2000 + M), s_first[si]))
+    ys = [torch.empty((M, N), device=dev, dtype=torch.float16) for (K, N) in shapes]
+    torch.cuda.synchronize()
+    t_build = time.time() - t_build
+
+    launches_per_step = nlayers * len(shapes)
+    bytes_per_step = nlayers * sum(wl.algorithmic_bytes(M, N, K, G) for (K, N) in shapes)
+
+    def step():
+        for per in layers:
+            for si, (p, sc, z) in enumerate(per):
+                sqp.w4a16_gemm(xs[si], p, sc, z, G, out=ys[si])
+
+    step()  # first call: lets the library set up its workspace outside any capture
+    torch.cuda.synchronize()
+    graph = None
+    if not args.no_graph:
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                step()
+        torch.cuda.synchronize()
+    run = graph.replay if graph is not None else step
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall * 1e3 / args.steps
+    value = bytes_per_step / (wall / args.steps) / 1e9
+
+    # dominant kernel: the decode GEMM; average launch duration from the HIP events
+    avg_launch_s = ev_ms * 1e-3 / (args.steps * launches_per_step)
+    bytes_per_launch = bytes_per_step / launches_per_step
+    achieved = bytes_per_launch / avg_launch_s / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                "kernel": "w4a16_decode_kernel", "avg_launch_us": round(avg_launch_s * 1e6, 2),
+                "algorithmic_bytes_per_launch": round(bytes_per_launch)}
+
+    extra = {}
+    if not args.no_extra:
+        extra = side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, G)
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(np, torch, wl, shapes, layers, xs, M, G)
+
+    out = {
+        "metric": "W4A16 GEMM: HBM GB/s at M<=16 (% of peak); TFLOP/s at M=2048 (% MFMA)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 x int4 -> f32 accumulate", "data": "synthetic",
+        "config": {"workload": "Code Llama-%s-shaped decode sweep, M=%d, %d layers x 4 linears, group 128, "
+                               "weights resident (%.2f GB algorithmic per step)" % (args.model.upper(), M, nlayers, bytes_per_step / 1e9),
+                   "launch": "hip-graph replay" if graph is not None else "python launches",
+                   "build_s": round(t_build, 1)},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "extra": extra,
+    }
+    print(json.dumps(out))
+
+
+def _time(torch, fn, iters):
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / iters
+
+
+def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, G):
+    """Context figures outside the headline: M=1 decode sweep, prefill at M=2048 (TFLOP/s
+    against the fp16 MFMA peak) and the companion kernels on the 22016x8192 weight."""
+    extra = {}
+    # decode at M=1 over all resident layers
+    M = 1
+    xs = [sqp.smooth_apply_x(activation(M, K, 2000 + M), s_first[si]) for si, (K, N) in enumerate(shapes)]
+    ys = [torch.empty((M, N), device=dev, dtype=torch.float16) for (K, N) in shapes]
+
+    def sweep():
+        for per in layers:
+            for si, (p, sc, z) in enumerate(per):
+                sqp.w4a16_gemm(xs[si], p, sc, z, G, out=ys[si])
+    t = _time(torch, sweep, 3)
+    b = len(layers) * sum(wl.algorithmic_bytes(M, N, K, G) for (K, N) in shapes)
+    extra["decode_m1_gbs"] = round(b / t / 1e9, 1)
+    extra["decode_m1_pct_hbm_peak"] = round(100 * b / t / 1e9 / HBM_PEAK_GBS, 2)
+    # prefill, M = 2048, the four shapes, rotating over the resident layers
+    M = 2048
+    pre = {}
+    flops_total, t_total = 0.0, 0.0
+    for si, (K, N) in enumerate(shapes):
+        x = sqp.smooth_apply_x(activation(M, K, 2000 + M), s_first[si])
+        y = torch.empty((M, N), device=dev, dtype=torch.float16)
+        nl = min(len(layers), 8)
+        state = {"i": 0}
+
+        def one():
+            p, sc, z = layers[state["i"] % nl][si]
+            state["i"] += 1
+            sqp.w4a16_gemm(x, p, sc, z, G, out=y)
+        t = _time(torch, one, nl)
+        fl = wl.gemm_flops(M, N, K)
+        pre["%dx%d" % (K, N)] = round(fl / t / 1e12, 1)
+        flops_total += fl
+        t_total += t
+        del x, y
+    extra["prefill_m2048_tflops_by_shape"] = pre
+    extra["prefill_m2048_tflops"] = round(flops_total / t_total / 1e12, 1)
+    extra["prefill_m2048_pct_mfma_peak"] = round(100 * flops_total / t_total / 1e12 / MFMA_F16_PEAK_TFLOPS, 2)
+    # companion kernels on the largest weight (22016 x 8192)
+    K, N = shapes[3]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    w = (torch.randn((K, N), device=dev, generator=gen, dtype=torch.float32) * 0.02).half()
+    xcal = activation(wl.T_CAL, K, 3000)
+    s = torch.empty(K, device=dev, dtype=torch.float32)
+    t = _time(torch, lambda: sqp.smooth_scales(xcal, w, wl.ALPHA, out=s), 5)
+    extra["smooth_scales_22016x8192_us"] = round(t * 1e6, 1)
+    extra["smooth_scales_gbs"] = round((2.0 * K * N + 2.0 * wl.T_CAL * K) / t / 1e9, 1)
+    out = sqp.quantize_pack(w, G)
+    t = _time(torch, lambda: sqp.quantize_pack(w, G, out=out), 5)
+    extra["quantize_pack_22016x8192_us"] = round(t * 1e6, 1)
+    extra["quantize_pack_gbs"] = round((2.0 * K * N + K * N * (0.5 + 3.0 / G)) / t / 1e9, 1)
+    return extra
+
+
+def cpu_baseline(np, torch, wl, shapes, layers, xs, M, G):
+    """The CPU oracle (fp32-accumulate variant, as it stands) on a bounded sample of the
+    same workload: layer 0, the 8192->8192 and 8192->10240 linears, at the same M."""
+    import oracle
+    oracle.lib()
+    nl = min(len(layers), 12)
+    t_total, b_total = 0.0, 0.0
+    for layer in range(nl):
+        for si, (K, N) in enumerate(shapes):
+            p, sc, z = layers[layer][si]
+            x = xs[si].cpu().numpy()
+            pn = p.cpu().numpy().view(np.uint32)
+            scn = sc.cpu().numpy()
+            zn = z.cpu().numpy()
+            t0 = time.perf_counter()
+            oracle.w4a16_gemm_f32(x, pn, scn, zn, G)
+            t_total += time.perf_counter() - t0
+            b_total += wl.algorithmic_bytes(M, N, K, G)
+    return {"value": round(b_total / t_total / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "layers 0..%d of the same sweep (all 4 linears, M=%d), one call each: %.1f s of CPU time" %
+                      (nl - 1, M, t_total)}
+
+
+if __name__ == "__main__":
+    main()
