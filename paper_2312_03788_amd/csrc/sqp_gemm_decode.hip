@@ -28,48 +28,9 @@
 #include <type_traits>
 
 #include "sqp_common.h"
+#include "sqp_w4_unpack.h"
 
 namespace {
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-// Constants of the nibble unpack, held in registers: v_and_or_b32 cannot take literals.
-struct UnpackConsts {
-    uint32_t mask_lo, mask_hi, magic_lo, magic_hi;
-};
-
-// packed word (8 codes of one column) -> 8 exact fp16 values (code - Z), in the order
-// (k0,k4),(k1,k5),(k2,k6),(k3,k7).  neg_hi = -(1024 + Z), neg_lo = -(64 + Z), both halves.
-// 1 shift + 4 and-or + 4 packed adds.
-__device__ __forceinline__ h16x8 dequant_word(uint32_t w, h16x2 neg_hi, h16x2 neg_lo, const UnpackConsts &uc)
-{
-    const uint32_t w8 = w >> 8;
-    uint32_t t0, t1, t2, t3;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(t0) : "v"(w), "v"(uc.mask_lo), "v"(uc.magic_lo));
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(t1) : "v"(w), "v"(uc.mask_hi), "v"(uc.magic_hi));
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(t2) : "v"(w8), "v"(uc.mask_lo), "v"(uc.magic_lo));
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(t3) : "v"(w8), "v"(uc.mask_hi), "v"(uc.magic_hi));
-    h16x2 b0 = __builtin_bit_cast(h16x2, t0) + neg_hi;
-    h16x2 b1 = __builtin_bit_cast(h16x2, t1) + neg_lo;
-    h16x2 b2 = __builtin_bit_cast(h16x2, t2) + neg_hi;
-    h16x2 b3 = __builtin_bit_cast(h16x2, t3) + neg_lo;
-    h16x8 r;
-    r.s0 = b0.x; r.s1 = b0.y; r.s2 = b1.x; r.s3 = b1.y;
-    r.s4 = b2.x; r.s5 = b2.y; r.s6 = b3.x; r.s7 = b3.y;
-    return r;
-}
-
-// 8 consecutive-k activations (x0..x7 as four dwords) -> the nibble order above.
-__device__ __forceinline__ h16x8 permute_x(const u32x4 &v)
-{
-    u32x4 p;
-    p.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);  // (x0, x4)
-    p.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);  // (x1, x5)
-    p.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);  // (x2, x6)
-    p.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);  // (x3, x7)
-    return __builtin_bit_cast(h16x8, p);
-}
 
 struct Workspace {
     float *partial;      // [tiles][SPLIT][NW][REGS][64]
@@ -120,7 +81,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     for (int mt = 0; mt < MT; mt++)
 #pragma unroll
         for (int t = 0; t < 4; t++) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const UnpackConsts uc = {0x000f000fu, 0x00f000f0u, 0x64006400u, 0x54005400u};
+    const UnpackConsts uc = SQP_UNPACK_CONSTS;
 
     struct Stage {
         u32x4 w[KSPG];
@@ -216,11 +177,9 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         float delta[4];
 #pragma unroll
         for (int c = 0; c < 4; c++) {
-            // fp16 bit patterns: 1024 + Z is 0x6400 + Z and 64 + Z is 0x5400 + 16 Z (Z <= 15);
-            // with the sign bit, replicated into both halves
             const uint32_t z = (s.zr >> (8 * c)) & 0xffu;
-            neg_hi[c] = __builtin_bit_cast(h16x2, z * 0x00010001u + 0xe400e400u);
-            neg_lo[c] = __builtin_bit_cast(h16x2, z * 0x00100010u + 0xd400d400u);
+            neg_hi[c] = neg_hi_of(z);
+            neg_lo[c] = neg_lo_of(z);
             const h16x2 sv = __builtin_bit_cast(h16x2, (uint32_t)s.sc[c >> 1]);
             delta[c] = live ? (float)((c & 1) ? sv.y : sv.x) : 0.f;
         }

@@ -125,3 +125,49 @@ def _layer_cached(orc, M, K, N, shape_idx):
     s, p, sc, z = _cache[key]
     x = wl.activation(M, K, seed=2000 + M)
     return orc.smooth_apply_x(x, s), p, sc, z
+
+
+# ---------------------------------------------------------------- prefill (M > 64)
+
+@pytest.mark.parametrize("M,K,N,group", [
+    (65, 256, 264, 128), (256, 512, 256, 64), (300, 1024, 520, 128), (130, 384, 72, 64),
+    (129, 512, 136, 256), (100, 128, 64, 32), (257, 192, 8, 64), (512, 2048, 1000, 128)])
+def test_prefill_shapes(orc, sqp, M, K, N, group):
+    """Tiled matrix-core path: full-output parity on shapes spanning several tiles with
+    ragged edges in M and N, several group sizes (32 takes the fallback path)."""
+    print("case prefill", M, K, N, group, flush=True)
+    xs, p, sc, z = _layer(orc, M, K, N, group)
+    _check(orc, sqp, xs, p, sc, z, group)
+
+
+def test_prefill_integer_exact(orc, sqp):
+    """step = 1, Z = 0, small integer activations: exact integer product."""
+    rng = np.random.Generator(np.random.PCG64(4))
+    M, N, K, g = 300, 320, 256, 128
+    q = rng.integers(0, 16, size=(K, N))
+    x = rng.integers(-4, 5, size=(M, K))
+    p = np.zeros((K // 8, N), np.uint32)
+    for i in range(8):
+        p |= q[i::8].astype(np.uint32) << np.uint32(4 * i)
+    ones = np.ones((K // g, N), np.float16)
+    zz = np.zeros((K // g, N), np.uint8)
+    y = host(sqp.w4a16_gemm(dev(x.astype(np.float16)), dev(p), dev(ones), dev(zz), g))
+    assert np.array_equal(y.astype(np.int64), x @ q)
+
+
+def test_prefill_full_size_sampled(orc, sqp):
+    """34B-shaped 8192 -> 8192 at M = 2048 (the launch configuration the benchmark times):
+    the oracle evaluates 24 seeded rows plus the first and last row over all N; every sampled
+    element is the full-K definition.  Run twice: the result must be bit-identical."""
+    K, N, M = 8192, 8192, 2048
+    print("case prefill full", M, K, N, flush=True)
+    xs, p, sc, z = _layer_cached(orc, M, K, N, 1)
+    rng = np.random.Generator(np.random.PCG64(12))
+    rows = np.unique(np.concatenate([[0, M - 1, 255, 256], rng.choice(M, 24, replace=False)]))
+    y_ref, t_ref = orc.w4a16_gemm_ref(np.ascontiguousarray(xs[rows]), p, sc, z, 128)
+    dp, dsc, dz, dx = dev(p), dev(sc), dev(z), dev(xs)
+    y = host(sqp.w4a16_gemm(dx, dp, dsc, dz, 128))
+    y2 = host(sqp.w4a16_gemm(dx, dp, dsc, dz, 128))
+    assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
+    ok, worst, nbad = gemm_tolerance_ok(orc, y[rows], y_ref, t_ref)
+    assert ok, "worst err/tol %.3f, %d elements out of tolerance" % (worst, nbad)
