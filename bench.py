@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch from Python instead of replaying a HIP graph")
     ap.add_argument("--no-extra", action="store_true", help="skip the M=1 / prefill / companion side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (known size: calibrates the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -104,6 +107,19 @@ def main():
         for per in layers:
             for si, (p, sc, z) in enumerate(per):
                 sqp.w4a16_gemm(xs[si], p, sc, z, G, out=ys[si])
+
+    if args.calib_copy:
+        import ctypes
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        L = sqp.lib()
+        L.sqp_debug_plain_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        for _ in range(3):
+            rc = L.sqp_debug_plain_copy(src.data_ptr(), dst.data_ptr(), src.numel() * 4,
+                                        torch.cuda.current_stream().cuda_stream)
+            assert rc == 0
+        torch.cuda.synchronize()
+        del src, dst
 
     step()  # first call: lets the library set up its workspace outside any capture
     torch.cuda.synchronize()

@@ -17,6 +17,21 @@ extern "C" const char *sqp_status_string(int status)
     }
 }
 
+// Plain device copy (16 bytes per lane, grid-stride): a kernel of known traffic that the
+// benchmark can run to calibrate hardware byte counters.  Benchmark hook, not part of the ABI.
+__global__ void __launch_bounds__(256) plain_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < n; i += stride) dst[i] = src[i];
+}
+extern "C" int sqp_debug_plain_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (!src || !dst || (bytes & 15)) return SQP_ERR_SHAPE;
+    plain_copy_kernel<<<8192, 256, 0, (hipStream_t)stream>>>((const uint4 *)src, (uint4 *)dst, bytes / 16);
+    return sqp_launch_status();
+}
+
 static int g_decode_max_m = 64;
 // Test/benchmark hook: rows up to which the weight-streaming path is used.
 extern "C" void sqp_debug_set_decode_max_m(int m) { g_decode_max_m = m; }
