@@ -229,11 +229,12 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // weights of chunk g+2 into the stage just freed (stage index static: the loop is unrolled
     // by D), consume chunk g.  The pipeline is primed by issuing chunks g0 and g0+1.
     // The loop body is free of branches: the chunk count is rounded up to a multiple of D,
-    // loads past the range are clamped to a valid chunk (they hit data a neighbour streams
-    // anyway) and such chunks enter the sum with a step of 0.  Every iteration thus issues the
+    // loads past the range are clamped to the range's last chunk (cache hits, no extra HBM
+    // traffic) and such chunks enter the sum with a step of 0.  Every iteration thus issues the
     // same OX + OW loads, and since loads complete in issue order "at most OX + OW loads
     // outstanding" means all but the previous iteration's have landed.
-    auto gc = [&](int g) { return g < chunks ? g : chunks - 1; };
+    const int glast = g1 > g0 ? g1 - 1 : (g0 < chunks ? g0 : chunks - 1);
+    auto gc = [&](int g) { return g < glast ? g : glast; };  // past the range: this workgroup's own last chunk again (a cache hit)
     Stage st[D];
     issue_x(0, gc(g0));
     issue_w(st[0], gc(g0));
@@ -290,42 +291,67 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     }
 
     // ---- cross-workgroup: the last arrival adds the SPLIT partial tiles in split order.
-    // Partials travel as device-scope relaxed atomic stores/loads (written through and read
-    // past the per-XCD L2), so no cache-wide write-back or invalidate is needed: each thread
+    // Partials travel as device-scope (sc1) 16-byte stores and loads, written through and read
+    // past the per-XCD L2, so no cache-wide write-back or invalidate is needed: each thread
     // waits for its own stores to complete, the barrier collects the workgroup, and only then
-    // is the ticket taken.
-    float *mine = ws.partial + (((size_t)tile * split + sidx) * NW + wave) * (REGS * 64) + lane;
+    // is the ticket taken.  Layout: [tile][split][wave][Q][lane][4] floats (each instruction
+    // moves 1 KB contiguous per wave).
+    constexpr int Q = REGS / 4;                         // 16-byte pieces per lane
+    constexpr int SB = MT == 1 ? 4 : (MT == 2 ? 2 : 1);  // partials fetched per round trip
+    {
+        float *mine = ws.partial + (((size_t)tile * split + sidx) * NW + wave) * (64 * REGS) + lane * 4;
 #pragma unroll
-    for (int mt = 0; mt < MT; mt++)
+        for (int mt = 0; mt < MT; mt++)
 #pragma unroll
-        for (int t = 0; t < 4; t++)
-#pragma unroll
-            for (int r = 0; r < 4; r++)
-                __hip_atomic_store(mine + ((mt * 4 + t) * 4 + r) * 64, acc[mt][t][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            for (int t = 0; t < 4; t++)
+                asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(mine + (mt * 4 + t) * 256), "v"(acc[mt][t]) : "memory");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     __syncthreads();
     if (threadIdx.x == 0) ticket_s = __hip_atomic_fetch_add(&ws.tickets[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket_s != (unsigned)(split - 1)) return;
-    if (nout < N) {
-        const float *base = ws.partial + (((size_t)tile * split) * NW + wave) * (REGS * 64) + lane;
+    {
+        const float *base = ws.partial + (((size_t)tile * split) * NW + wave) * (64 * REGS) + lane * 4;
+        const size_t sstride = (size_t)NW * 64 * REGS;
+        f32x4 sum[Q];
 #pragma unroll
-        for (int mt = 0; mt < MT; mt++)
+        for (int q = 0; q < Q; q++) sum[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int s0 = 0; s0 < split; s0 += SB) {
+            f32x4 tmp[SB][Q];
 #pragma unroll
-            for (int r = 0; r < 4; r++) {
-                float v[4] = {0.f, 0.f, 0.f, 0.f};
-                for (int s = 0; s < split; s++)
+            for (int j = 0; j < SB; j++)
+                if (s0 + j < split) {
 #pragma unroll
-                    for (int t = 0; t < 4; t++)
-                        v[t] += __hip_atomic_load(base + (size_t)s * NW * (REGS * 64) + ((mt * 4 + t) * 4 + r) * 64,
-                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const int m = mt * 16 + 4 * lk + r;
-                if (m < M) {
-                    h16x4 o;
-                    o.x = (h16)v[0]; o.y = (h16)v[1]; o.z = (h16)v[2]; o.w = (h16)v[3];
-                    *reinterpret_cast<h16x4 *>(y + (size_t)m * N + nout) = o;
+                    for (int q = 0; q < Q; q++)
+                        asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(tmp[j][q]) : "v"(base + (size_t)(s0 + j) * sstride + q * 256) : "memory");
                 }
-            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int j = 0; j < SB; j++)
+#pragma unroll
+                for (int q = 0; q < Q; q++) asm volatile("" : "+v"(tmp[j][q]));
+#pragma unroll
+            for (int j = 0; j < SB; j++)
+                if (s0 + j < split) {
+#pragma unroll
+                    for (int q = 0; q < Q; q++) sum[q] += tmp[j][q];
+                }
+        }
+        if (nout < N) {
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    const int m = mt * 16 + 4 * lk + r;
+                    if (m < M) {
+                        h16x4 o;
+                        o.x = (h16)sum[mt * 4 + 0][r]; o.y = (h16)sum[mt * 4 + 1][r];
+                        o.z = (h16)sum[mt * 4 + 2][r]; o.w = (h16)sum[mt * 4 + 3][r];
+                        *reinterpret_cast<h16x4 *>(y + (size_t)m * N + nout) = o;
+                    }
+                }
+        }
     }
     if (threadIdx.x == 0)  // ready for the next launch on this stream
         __hip_atomic_store(&ws.tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -389,6 +415,8 @@ int get_workspace(Workspace *out, hipStream_t st)
     return SQP_OK;
 }
 
+static int g_dyn_lds = 0;  // benchmark hook: extra LDS per workgroup (limits workgroups per compute unit)
+
 template <int MT, int NW, int KSPG>
 int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t *packed, const h16 *scales,
            const uint8_t *zeros, h16 *y, hipStream_t st)
@@ -407,7 +435,7 @@ int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t
         int rc = get_workspace(&ws, st);
         if (rc) return rc;
     }
-    w4a16_decode_kernel<MT, NW, KSPG><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws);
+    w4a16_decode_kernel<MT, NW, KSPG><<<dim3(tiles, split), NW * 64, g_dyn_lds, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws);
     return sqp_launch_status();
 }
 
@@ -415,18 +443,19 @@ struct Plan {
     int nw, split;
 };
 
-// Strips per workgroup and K split, from sweeps on Code Llama shapes: about a thousand waves
-// in flight keep the memory system busy; beyond that the fp32 partial tiles of the K split
-// cost more than the extra parallelism brings.  Very wide layers take two strips per
-// workgroup (more, smaller workgroups balance better over 256 compute units).
+// Strips per workgroup and K split, from sweeps on Code Llama shapes.  Four strips per
+// workgroup share one copy of the activations.  Narrow layers (up to 128 column tiles) run
+// best with one workgroup per compute unit (256 in all), each walking a long K range; wider
+// ones with two to three workgroups per unit.  More splits than that cost more in fp32
+// partial tiles than the extra parallelism brings.
 Plan make_plan(int M, int N, int K, int chunk)
 {
     const int chunks = K / chunk;
     Plan p;
-    p.nw = N >= 32768 ? 2 : 4;
+    p.nw = 4;
     const int tiles = (N + 64 * p.nw - 1) / (64 * p.nw);
-    const int target_waves = p.nw == 2 ? 1400 : 1000;
-    int want = (target_waves + tiles * p.nw / 2) / (tiles * p.nw);
+    const int target = tiles <= 128 ? 256 : 704;
+    int want = (target + tiles / 2) / tiles;
     int max_split = chunks / 4;  // at least four chunks per workgroup
     if (max_split < 1) max_split = 1;
     if (want > max_split) want = max_split;
@@ -440,6 +469,7 @@ template <int MT, int KSPG>
 int dispatch_mt(const Plan &p, int M, int N, int K, int cpg, const h16 *x, const uint32_t *packed, const h16 *scales,
                 const uint8_t *zeros, h16 *y, hipStream_t st)
 {
+    if (p.nw == 1) return launch<MT, 1, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
     if (p.nw == 2) return launch<MT, 2, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
     if constexpr (MT < 4)  // eight waves of the 64-row variant would not fit the register file
         if (p.nw == 8) return launch<MT, 8, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
@@ -461,6 +491,7 @@ int dispatch_kspg(const Plan &p, int M, int N, int K, int cpg, const h16 *x, con
 static int g_force_split = 0;
 static Plan g_force_plan = {0, 0};
 extern "C" void sqp_debug_set_decode_split(int split) { g_force_split = split; }
+extern "C" void sqp_debug_set_decode_dyn_lds(int bytes) { g_dyn_lds = bytes; }
 extern "C" void sqp_debug_set_decode_plan(int nw, int split) { g_force_plan = Plan{nw, split}; }
 
 int sqp_gemm_generic(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
