@@ -1,17 +1,22 @@
 // Tiled matrix-core W4A16 GEMM for large M (prefill): y = x * w_hat, Eq. 3 of
 // arXiv 2312.03788 with w_hat = fp16((code - Z) * Delta) of Eq. 1, group-wise along K.
 //
-// A workgroup of 8 waves computes a 256 x 256 tile of y; wave (wm, wn) owns 128 rows x 64
-// columns of it as 4 x 2 accumulator tiles of v_mfma_f32_32x32x16_f16.
-//   - Weights never pass through LDS: one dwordx2 load per lane fetches, for k-block
-//     (lane / 32), the packed words of 2 adjacent columns; a word is 8 consecutive k of one
+// A workgroup of 4 waves (one per SIMD, the whole register file each) computes a 256 x 256
+// tile of y; wave (wm, wn) owns 128 rows x 128 columns of it as 4 x 4 accumulator tiles of
+// v_mfma_f32_32x32x16_f16 (256 fp32 registers per lane).
+//   - Weights never pass through LDS: one dwordx4 load per lane fetches, for k-block
+//     (lane / 32), the packed words of 4 adjacent columns; a word is 8 consecutive k of one
 //     column, i.e. one lane's B operand of the 32x32x16 MFMA (column = lane % 32).  The word
 //     is unpacked in registers to the fp16 dequantised weights (13 VALU ops) and each B
-//     operand feeds 4 MFMAs (the 4 row tiles).
+//     operand feeds 4 MFMAs (the 4 row tiles); each activation fragment feeds 4 as well
+//     (4.25 VALU ops per MFMA).
 //   - Activations are the shared operand: a 256 x 64 slice of x per stage is copied once per
 //     workgroup straight into a three-slot LDS ring (direct global->LDS loads of whole
 //     128-byte lines, pieces XOR-swizzled so that the 16-byte reads of one k-step spread over
 //     all banks) and every wave reads its A operands from there.
+//   - With a single wave per SIMD nothing else hides latency, so the k-steps are
+//     software-pipelined by hand: while the 16 MFMAs of one k-step run, the activation
+//     fragments of the next are on their way from LDS and the next weight words are unpacked.
 //   - Loads, waits and the per-stage barrier are explicit (assembly), as in the decode
 //     kernel: two stages stay in flight while one is consumed.
 #include <type_traits>
@@ -23,56 +28,54 @@ namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
 
-__global__ void __launch_bounds__(512)
+__global__ void __launch_bounds__(256)
 w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, const uint32_t *__restrict__ packed,
-                     const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y)
+                        const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y)
 {
     constexpr int D = 3, XD = 3;
-    constexpr int XSTAGE = BM * BK * 2;        // 32 KB: 32 blocks of 8 rows x 128 bytes
-    constexpr int OX = 4;                       // direct loads per wave per stage (32 blocks / 8 waves)
-    constexpr int OW = 4 + 2;                   // 4 k-steps of packed words + steps + zero points
+    constexpr int XSTAGE = BM * BK * 2;   // 32 KB: 32 blocks of 8 rows x 128 bytes
+    constexpr int OX = 8;                  // direct loads per wave per stage (32 blocks / 4 waves)
+    constexpr int OW = 4 + 2;
     __shared__ __attribute__((aligned(1024))) unsigned char xring[XD * XSTAGE];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, kb = lane >> 5;
     const int m0 = blockIdx.y * BM;
-    const int n0 = blockIdx.x * BN + wn * 64;
+    const int n0 = blockIdx.x * BN + wn * 128;
     const int stages = K / BK;
 
-    // lanes past the last column read column 0 instead; their results are never stored
-    int ncol = n0 + 2 * l32;
+    int ncol = n0 + 4 * l32;
     if (ncol >= N) ncol = 0;
 
-    f32x16 acc[4][2];
+    f32x16 acc[4][4];
 #pragma unroll
     for (int mt = 0; mt < 4; mt++)
 #pragma unroll
-        for (int t = 0; t < 2; t++)
+        for (int t = 0; t < 4; t++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[mt][t][r] = 0.f;
     const UnpackConsts uc = SQP_UNPACK_CONSTS;
 
     struct Stage {
-        u32x2 w[4];   // per k-step: packed words of the lane's 2 columns
-        uint32_t sc;  // 2 fp16 steps
-        uint32_t zr;  // 2 zero points, one byte each
+        u32x4 w[4];   // per k-step: packed words of the lane's 4 columns
+        u32x2 sc;     // 4 fp16 steps
+        uint32_t zr;  // 4 zero points, one byte each
     };
-
     const uint32_t voff_w = (uint32_t)(kb * N + ncol) * 4u;
     const uint32_t voff_s = (uint32_t)ncol * 2u, voff_z = (uint32_t)ncol;
     auto issue_w = [&](Stage &s, int st) {
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) {
             const uint32_t *base = packed + (size_t)(st * 4 + ks) * 2 * N;  // wave-uniform
-            asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
         }
         const int gs = (st * BK) / group;
         const h16 *sbase = scales + (size_t)gs * N;
         const uint8_t *zbase = zeros + (size_t)gs * N;
-        asm volatile("global_load_dword %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sbase) : "memory");
-        asm volatile("global_load_ushort %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zbase) : "memory");
+        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sbase) : "memory");
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zbase) : "memory");
     };
     auto landed = [&](Stage &s, auto after) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(after)::value) : "memory");
@@ -82,13 +85,14 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
         asm volatile("" : "+v"(s.zr));
     };
 
-    // Activations: wave w copies blocks w, w+8, w+16, w+24 of the stage.  Lane i of a block
-    // handles row i / 8 of the block and fetches piece (i % 8) ^ key(row) of that row's 128
-    // bytes, key(row) = (row / 2) % 8; the hardware puts lane i at byte 16*i of the block.
+    // Activations: wave w copies blocks w, w+4, ..., w+28 of the stage (a block = 8 rows x 128
+    // bytes).  Lane i of a block handles row i / 8 of the block and fetches piece
+    // (i % 8) ^ key(row) of that row's 128 bytes, key(row) = (row / 2) % 8; the hardware puts
+    // lane i at byte 16*i of the block.
     uint32_t xoff[OX];
 #pragma unroll
     for (int j = 0; j < OX; j++) {
-        const int b = wave + 8 * j;
+        const int b = wave + 4 * j;
         const int row = b * 8 + (lane >> 3);
         int grow = m0 + row;
         if (grow >= M) grow = M - 1;
@@ -96,64 +100,64 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
         xoff[j] = (uint32_t)grow * (uint32_t)K * 2u + (uint32_t)(piece * 16);
     }
     auto issue_x = [&](int slot, int st) {
-        const unsigned char *base = reinterpret_cast<const unsigned char *>(x + (size_t)st * BK);  // wave-uniform
+        const unsigned char *base = reinterpret_cast<const unsigned char *>(x + (size_t)st * BK);
 #pragma unroll
         for (int j = 0; j < OX; j++) {
-            unsigned char *dst = xring + slot * XSTAGE + (wave + 8 * j) * 1024;
+            unsigned char *dst = xring + slot * XSTAGE + (wave + 4 * j) * 1024;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + xoff[j]),
                                              (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
         }
     };
-    // LDS byte address of this lane's A fragment row in slot 0, row tile 0, before the piece;
-    // row tile mt is 32 rows = 4 blocks = 4096 bytes further
     const uint32_t xrd0 = (uint32_t)(size_t)xring +
                           (uint32_t)(((wm * 128 + l32) >> 3) * 1024 + ((wm * 128 + l32) & 7) * 128);
     const int xkey = (l32 >> 1) & 7;
 
-    auto compute = [&](const Stage &s, int slot, bool live) {
-        h16x2 neg_hi[2], neg_lo[2], delta[2];
+    auto read_a = [&](u32x4 (&xa)[4], int slot, int ks) {
+        const uint32_t poff = xrd0 + (uint32_t)(slot * XSTAGE) + (uint32_t)((((ks * 2 + kb) ^ xkey)) * 16);
 #pragma unroll
-        for (int t = 0; t < 2; t++) {
+        for (int mt = 0; mt < 4; mt++)
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(xa[mt]) : "v"(poff), "n"(mt * 4096) : "memory");
+    };
+    auto wait_a = [&](u32x4 (&xa)[4]) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int mt = 0; mt < 4; mt++) asm volatile("" : "+v"(xa[mt]));
+    };
+
+    auto compute = [&](const Stage &s, int slot, bool live) {
+        h16x2 neg_hi[4], neg_lo[4], delta[4];
+#pragma unroll
+        for (int t = 0; t < 4; t++) {
             const uint32_t z = (s.zr >> (8 * t)) & 0xffu;
             neg_hi[t] = neg_hi_of(z);
             neg_lo[t] = neg_lo_of(z);
-            const uint32_t d = live ? ((s.sc >> (16 * t)) & 0xffffu) * 0x00010001u : 0u;  // step 0: adds nothing
+            const uint32_t sw = (uint32_t)s.sc[t >> 1];
+            const uint32_t d = live ? ((sw >> (16 * (t & 1))) & 0xffffu) * 0x00010001u : 0u;  // step 0: adds nothing
             delta[t] = __builtin_bit_cast(h16x2, d);
         }
+        u32x4 xa[2][4];
+        h16x8 b[2][4];
+        read_a(xa[0], slot, 0);
+#pragma unroll
+        for (int t = 0; t < 4; t++) b[0][t] = dequant_word_scaled(s.w[0][t], neg_hi[t], neg_lo[t], delta[t], uc);
+        wait_a(xa[0]);
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) {
-            u32x2 wk = s.w[ks];
-            asm volatile("" : "+v"(wk));  // keeps the unpack of this k-step from being hoisted over earlier ones
-            h16x8 b[2];
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks < 3) read_a(xa[nxt], slot, ks + 1);
 #pragma unroll
-            for (int t = 0; t < 2; t++) b[t] = dequant_word_scaled(wk[t], neg_hi[t], neg_lo[t], delta[t], uc);
-            const uint32_t poff = (uint32_t)(slot * XSTAGE) + (uint32_t)((((ks * 2 + kb) ^ xkey)) * 16);
+            for (int mt = 0; mt < 4; mt++) {
+                const h16x8 a = permute_x(xa[cur][mt]);
 #pragma unroll
-            for (int mh = 0; mh < 4; mh += 2) {  // two row tiles at a time (register budget)
-                u32x4 xa[2];
-#pragma unroll
-                for (int i = 0; i < 2; i++) {
-                    const uint32_t a = xrd0 + (uint32_t)((mh + i) * 4096) + poff;
-                    asm volatile("ds_read_b128 %0, %1" : "=&v"(xa[i]) : "v"(a) : "memory");
-                }
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-                for (int i = 0; i < 2; i++) asm volatile("" : "+v"(xa[i]));  // no use ahead of the wait
-#pragma unroll
-                for (int i = 0; i < 2; i++) {
-                    const h16x8 a = permute_x(xa[i]);
-#pragma unroll
-                    for (int t = 0; t < 2; t++)
-                        acc[mh + i][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b[t], acc[mh + i][t], 0, 0, 0);
-                }
+                for (int t = 0; t < 4; t++)
+                    acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b[cur][t], acc[mt][t], 0, 0, 0);
+                if (ks < 3)  // the next k-step's weight word of column mt, unpacked in the MFMAs' shadow
+                    b[nxt][mt] = dequant_word_scaled(s.w[ks + 1][mt], neg_hi[mt], neg_lo[mt], delta[mt], uc);
             }
+            if (ks < 3) wait_a(xa[nxt]);
         }
     };
 
-    // Same software pipeline as the decode kernel: iteration s waits for everything issued up
-    // to iteration s-2, meets the other waves, issues stage s+2, consumes stage s.  Stage
-    // count rounded up to a multiple of D; stages past the end are clamped and enter with a
-    // step of 0.
     auto sc_ = [&](int st) { return st < stages ? st : stages - 1; };
     Stage stg[D];
     issue_x(0, sc_(0));
@@ -175,7 +179,6 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
             slot = slot + 1 == XD ? 0 : slot + 1;
         }
     }
-    // drain the clamped look-ahead loads; keep their registers allocated until they landed
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
     for (int j = 0; j < D; j++) {
@@ -186,14 +189,12 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
     }
 
     // epilogue: accumulator register r of tile (mt, t): row 8*(r/4) + 4*(lane/32) + r%4 of the
-    // 32-row tile, column 2*(lane%32) + t of the wave's 64.  The lane's coordinates are derived
-    // afresh (the empty asm hides the value from common-subexpression elimination) so that
-    // nothing of the epilogue occupies registers during the main loop.
+    // 32-row tile, column 4*(lane%32) + t of the wave's 128
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     const int e_l32 = tid & 31, e_kb = (tid >> 5) & 1, e_wave = tid >> 6;
-    const int nout = blockIdx.x * BN + (e_wave & 3) * 64 + 2 * e_l32;
-    const int mrow0 = blockIdx.y * BM + (e_wave >> 2) * 128 + 4 * e_kb;
+    const int nout = blockIdx.x * BN + (e_wave & 1) * 128 + 4 * e_l32;
+    const int mrow0 = blockIdx.y * BM + (e_wave >> 1) * 128 + 4 * e_kb;
     if (nout < N) {
         h16 *ycol = y + nout;
 #pragma unroll
@@ -202,10 +203,10 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
             for (int r = 0; r < 16; r++) {
                 const int m = mrow0 + mt * 32 + 8 * (r >> 2) + (r & 3);
                 if (m < M) {
-                    h16x2 o;
-                    o.x = (h16)acc[mt][0][r];
-                    o.y = (h16)acc[mt][1][r];
-                    *reinterpret_cast<h16x2 *>(ycol + (size_t)m * N) = o;
+                    h16x4 o;
+                    o.x = (h16)acc[mt][0][r]; o.y = (h16)acc[mt][1][r];
+                    o.z = (h16)acc[mt][2][r]; o.w = (h16)acc[mt][3][r];
+                    *reinterpret_cast<h16x4 *>(ycol + (size_t)m * N) = o;
                 }
             }
     }
@@ -218,7 +219,7 @@ int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_
 {
     if (group % BK == 0 && (M + BM - 1) / BM <= 65535) {
         dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
-        w4a16_prefill_kernel<<<grid, 512, 0, stream>>>(M, N, K, group, x, packed, scales, zeros, y);
+        w4a16_prefill_kernel<<<grid, 256, 0, stream>>>(M, N, K, group, x, packed, scales, zeros, y);
         return sqp_launch_status();
     }
     // group sizes the tiled kernel does not cover: the weight-streaming kernel, 64 rows at a time
