@@ -11,7 +11,7 @@
 //     of one column, which is exactly one lane's B operand of v_mfma_f32_16x16x32_f16
 //     (column = lane % 16, k-block = lane / 16).
 //   - The activations of a K chunk are fetched ONCE per workgroup, as whole 128-byte lines,
-//     by direct global->LDS loads into a three-slot ring, and every wave takes its A operands
+//     by direct global->LDS loads into a ring of D slots, and every wave takes its A operands
 //     from there (row = lane % 16, permuted to the nibble order of the unpack).
 //   - The codes become exact fp16 integers (code - Z) with 9 VALU ops per word: the nibbles
 //     are OR-ed into the mantissa of 1024.0 (bits 3:0) or 64.0 (bits 7:4) and the offset
@@ -19,7 +19,7 @@
 //   - The MFMA accumulates one chunk in fp32, then the step Delta (a per-lane scalar in the
 //     16x16 accumulator layout: column = lane % 16) scales it into the running sum:
 //     sum_k x (q - Z) Delta = Delta * sum_k x (q - Z).
-//   - Weight loads and all waits are written in assembly: two chunks of weights stay in
+//   - Weight loads and all waits are written in assembly: D - 1 chunks of weights stay in
 //     flight per wave while one is consumed, and the compiler's conservative waits (it cannot
 //     tell ring slots apart) would serialise that.
 // With SPLIT > 1 workgroups along K, fp32 partial tiles go to a workspace and the workgroup
@@ -29,6 +29,10 @@
 
 #include "sqp_common.h"
 #include "sqp_w4_unpack.h"
+
+#ifndef SQP_DECODE_DEPTH
+#define SQP_DECODE_DEPTH 4
+#endif
 
 namespace {
 
@@ -41,13 +45,14 @@ struct Workspace {
 // KSPG: k-steps (of 32) per chunk; a quantisation group is cpg chunks (cpg = 1 unless the
 // group is a multiple of 128 above 128).
 template <int MT, int NW, int KSPG>
-__global__ void __launch_bounds__(NW * 64)
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MT == 1 && NW >= 4 ? 3 : 1)))
 w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, const uint32_t *__restrict__ packed,
                     const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y,
                     Workspace ws)
 {
-    constexpr int D = 3;                   // register stages of packed weights
-    constexpr int XD = 3;                  // LDS slots of activations
+    constexpr int D = SQP_DECODE_DEPTH;    // register stages of packed weights
+    constexpr int XD = D;                  // LDS slots of activations
+    constexpr int P = D - 1;               // chunks in flight ahead of the one being consumed
     constexpr int REGS = MT * 4 * 4;       // fp32 accumulator registers per lane
     constexpr int BN = 64 * NW;
     // One chunk of x in LDS: MT*16 rows of KSPG*64 bytes, stored as 1 KB blocks, one per
@@ -58,7 +63,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     constexpr int XSTAGE = XBLOCKS * 1024;
     constexpr int OX = (XBLOCKS + NW - 1) / NW;  // direct loads per wave per chunk
     constexpr int OW = KSPG + 2;                 // weight-side loads per wave per chunk
-    static_assert(OX + OW < 64, "vmcnt field");
+    static_assert((P - 1) * (OX + OW) < 64, "vmcnt field");
     __shared__ __attribute__((aligned(1024))) unsigned char xring[XD * XSTAGE];
     __shared__ unsigned ticket_s;
 
@@ -223,23 +228,25 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
                 for (int r = 0; r < 4; r++) acc[mt][t][r] = fmaf(delta[t], accg[mt][t][r], acc[mt][t][r]);
     };
 
-    // Software pipeline over the chunk range.  Iteration g: wait for everything issued up to
-    // iteration g-2 (weights and this wave's part of x of chunk g), meet the other waves (now
-    // all of x(g) is in LDS and nobody reads slot (g+2) % 3 any more), issue x(g+2) and the
-    // weights of chunk g+2 into the stage just freed (stage index static: the loop is unrolled
-    // by D), consume chunk g.  The pipeline is primed by issuing chunks g0 and g0+1.
+    // Software pipeline over the chunk range, P = D - 1 chunks ahead.  Iteration g: wait for
+    // everything issued up to iteration g-P (weights and this wave's part of x of chunk g),
+    // meet the other waves (now all of x(g) is in LDS and nobody reads the slot of chunk g-1 any
+    // more), issue x(g+P) and the weights of chunk g+P into that slot and the stage just freed
+    // (stage index static: the loop is unrolled by D), consume chunk g.  The pipeline is primed
+    // by issuing chunks g0 .. g0+P-1.
     // The loop body is free of branches: the chunk count is rounded up to a multiple of D,
     // loads past the range are clamped to the range's last chunk (cache hits, no extra HBM
     // traffic) and such chunks enter the sum with a step of 0.  Every iteration thus issues the
-    // same OX + OW loads, and since loads complete in issue order "at most OX + OW loads
-    // outstanding" means all but the previous iteration's have landed.
+    // same OX + OW loads, and since loads complete in issue order "at most (P-1)(OX + OW) loads
+    // outstanding" means all but the last P-1 iterations' have landed.
     const int glast = g1 > g0 ? g1 - 1 : (g0 < chunks ? g0 : chunks - 1);
     auto gc = [&](int g) { return g < glast ? g : glast; };  // past the range: this workgroup's own last chunk again (a cache hit)
     Stage st[D];
-    issue_x(0, gc(g0));
-    issue_w(st[0], gc(g0));
-    issue_x(1, gc(g0 + 1));
-    issue_w(st[1], gc(g0 + 1));
+#pragma unroll
+    for (int j = 0; j < P; j++) {
+        issue_x(j, gc(g0 + j));
+        issue_w(st[j], gc(g0 + j));
+    }
     int slot = 0;  // ring slot of chunk g
     const int nblk = (g1 - g0 + D - 1) / D;
     for (int b = 0; b < nblk; b++) {
@@ -247,11 +254,11 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 #pragma unroll
         for (int d = 0; d < D; d++) {
             const int gg = g + d;
-            landed(st[d], std::integral_constant<int, OX + OW>());
+            landed(st[d], std::integral_constant<int, (P - 1) * (OX + OW)>());
             asm volatile("s_barrier" ::: "memory");
-            const int fill = slot >= 1 ? slot - 1 : XD - 1;  // (slot + 2) % 3
-            issue_x(fill, gc(gg + 2));
-            issue_w(st[(d + 2) % D], gc(gg + 2));
+            const int fill = slot >= 1 ? slot - 1 : XD - 1;  // (slot + P) % XD
+            issue_x(fill, gc(gg + P));
+            issue_w(st[(d + P) % D], gc(gg + P));
             compute(st[d], slot, gg < g1);
             slot = slot + 1 == XD ? 0 : slot + 1;
         }
