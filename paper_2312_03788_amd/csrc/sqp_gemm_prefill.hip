@@ -32,7 +32,8 @@ __global__ void __launch_bounds__(256)
 w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, const uint32_t *__restrict__ packed,
                         const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y)
 {
-    constexpr int D = 3, XD = 3;
+    constexpr int D = 3;                   // register stages of packed weights (two in flight)
+    constexpr int XD = 4;                  // LDS slots of activations
     constexpr int XSTAGE = BM * BK * 2;   // 32 KB: 32 blocks of 8 rows x 128 bytes
     constexpr int OX = 8;                  // direct loads per wave per stage (32 blocks / 4 waves)
     constexpr int OW = 4 + 2;
@@ -45,6 +46,7 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
     const int m0 = blockIdx.y * BM;
     const int n0 = blockIdx.x * BN + wn * 128;
     const int stages = K / BK;
+    const int spg = group / BK;            // stages per quantisation group
 
     int ncol = n0 + 4 * l32;
     if (ncol >= N) ncol = 0;
@@ -63,19 +65,26 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
         u32x2 sc;     // 4 fp16 steps
         uint32_t zr;  // 4 zero points, one byte each
     };
+
+    // The loading side walks the stages with wave-uniform byte pointers that are advanced by
+    // constant strides (scalar adds only); past the last stage they stop, so that the padded
+    // stages of the branch-free loop re-read the last one (cache hits).
+    const unsigned char *wq = reinterpret_cast<const unsigned char *>(packed);
+    const unsigned char *sq = reinterpret_cast<const unsigned char *>(scales);
+    const unsigned char *zq = zeros;
+    const unsigned char *xq = reinterpret_cast<const unsigned char *>(x);
+    const long wrow2 = (long)N * 8;        // two packed rows (one k-step) in bytes
+    int ist = 0, kin = 0;                   // stage being issued, its position inside its group
     const uint32_t voff_w = (uint32_t)(kb * N + ncol) * 4u;
     const uint32_t voff_s = (uint32_t)ncol * 2u, voff_z = (uint32_t)ncol;
-    auto issue_w = [&](Stage &s, int st) {
+    auto issue_w = [&](Stage &s) {
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) {
-            const uint32_t *base = packed + (size_t)(st * 4 + ks) * 2 * N;  // wave-uniform
+            const unsigned char *base = wq + ks * wrow2;  // wave-uniform
             asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
         }
-        const int gs = (st * BK) / group;
-        const h16 *sbase = scales + (size_t)gs * N;
-        const uint8_t *zbase = zeros + (size_t)gs * N;
-        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sbase) : "memory");
-        asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zbase) : "memory");
+        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sq) : "memory");
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zq) : "memory");
     };
     auto landed = [&](Stage &s, auto after) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(after)::value) : "memory");
@@ -99,14 +108,22 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
         const int piece = (lane & 7) ^ ((row >> 1) & 7);
         xoff[j] = (uint32_t)grow * (uint32_t)K * 2u + (uint32_t)(piece * 16);
     }
-    auto issue_x = [&](int slot, int st) {
-        const unsigned char *base = reinterpret_cast<const unsigned char *>(x + (size_t)st * BK);
-#pragma unroll
-        for (int j = 0; j < OX; j++) {
-            unsigned char *dst = xring + slot * XSTAGE + (wave + 4 * j) * 1024;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + xoff[j]),
-                                             (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-        }
+    auto issue_x = [&](int slot, int j) {
+        unsigned char *dst = xring + slot * XSTAGE + (wave + 4 * j) * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xq + xoff[j]),
+                                         (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+    };
+    // all loads of the stage have been issued: step the pointers unless it was the last stage
+    auto advance = [&]() {
+        const bool more = ist + 1 < stages;
+        ist += more ? 1 : 0;
+        wq += more ? 4 * wrow2 : 0;
+        xq += more ? BK * 2 : 0;
+        kin += more ? 1 : 0;
+        const bool wrap = kin == spg;
+        kin = wrap ? 0 : kin;
+        sq += wrap ? (long)N * 2 : 0;
+        zq += wrap ? (long)N : 0;
     };
     const uint32_t xrd0 = (uint32_t)(size_t)xring +
                           (uint32_t)(((wm * 128 + l32) >> 3) * 1024 + ((wm * 128 + l32) & 7) * 128);
@@ -124,59 +141,98 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
         for (int mt = 0; mt < 4; mt++) asm volatile("" : "+v"(xa[mt]));
     };
 
-    auto compute = [&](const Stage &s, int slot, bool live) {
-        h16x2 neg_hi[4], neg_lo[4], delta[4];
+    // per-stage constants of the unpack: -(1024 + Z), -(64 + Z) and the step, each in both
+    // halves of a register; a stage past the end gets a step of 0 and adds nothing
+    h16x2 neg_hi[4], neg_lo[4], delta[4];
+    auto stage_consts = [&](const Stage &s, bool live) {
+        const uint32_t sel_even = live ? 0x01000100u : 0x0c0c0c0cu;  // byte selectors of v_perm_b32
+        const uint32_t sel_odd = live ? 0x03020302u : 0x0c0c0c0cu;   // (0x0c selects a zero byte)
 #pragma unroll
         for (int t = 0; t < 4; t++) {
             const uint32_t z = (s.zr >> (8 * t)) & 0xffu;
             neg_hi[t] = neg_hi_of(z);
             neg_lo[t] = neg_lo_of(z);
             const uint32_t sw = (uint32_t)s.sc[t >> 1];
-            const uint32_t d = live ? ((sw >> (16 * (t & 1))) & 0xffffu) * 0x00010001u : 0u;  // step 0: adds nothing
-            delta[t] = __builtin_bit_cast(h16x2, d);
-        }
-        u32x4 xa[2][4];
-        h16x8 b[2][4];
-        read_a(xa[0], slot, 0);
-#pragma unroll
-        for (int t = 0; t < 4; t++) b[0][t] = dequant_word_scaled(s.w[0][t], neg_hi[t], neg_lo[t], delta[t], uc);
-        wait_a(xa[0]);
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks < 3) read_a(xa[nxt], slot, ks + 1);
-#pragma unroll
-            for (int mt = 0; mt < 4; mt++) {
-                const h16x8 a = permute_x(xa[cur][mt]);
-#pragma unroll
-                for (int t = 0; t < 4; t++)
-                    acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b[cur][t], acc[mt][t], 0, 0, 0);
-                if (ks < 3)  // the next k-step's weight word of column mt, unpacked in the MFMAs' shadow
-                    b[nxt][mt] = dequant_word_scaled(s.w[ks + 1][mt], neg_hi[mt], neg_lo[mt], delta[mt], uc);
-            }
-            if (ks < 3) wait_a(xa[nxt]);
+            delta[t] = __builtin_bit_cast(h16x2, __builtin_amdgcn_perm(sw, sw, (t & 1) ? sel_odd : sel_even));
         }
     };
 
-    auto sc_ = [&](int st) { return st < stages ? st : stages - 1; };
+    // One continuous software pipeline over all k-steps.  While the 16 MFMAs of a k-step
+    // issue, the A fragments of the next k-step come from LDS and the next weight word is
+    // unpacked.  The hand-over to the next stage happens inside the last k-step of a stage
+    // (wait for the next stage's loads, barrier, new constants), so the first LDS reads and
+    // the first unpack of a stage are hidden like any other.  Ring discipline: the barrier in
+    // the last k-step of stage s-1 proves every wave has finished stage s-2, whose LDS slot
+    // (four slots) and weight registers (three stages) are refilled during stage s with the
+    // loads of stage s+2.
     Stage stg[D];
-    issue_x(0, sc_(0));
-    issue_w(stg[0], sc_(0));
-    issue_x(1, sc_(1));
-    issue_w(stg[1], sc_(1));
-    int slot = 0;
+    u32x4 xa[2][4];
+    h16x8 b[2][4];
+    issue_w(stg[0]);
+#pragma unroll
+    for (int j = 0; j < OX; j++) issue_x(0, j);
+    advance();
+    issue_w(stg[1]);
+#pragma unroll
+    for (int j = 0; j < OX; j++) issue_x(1, j);
+    advance();
+    landed(stg[0], std::integral_constant<int, OX + OW>());
+    asm volatile("s_barrier" ::: "memory");
+    stage_consts(stg[0], true);
+    read_a(xa[0], 0, 0);
+#pragma unroll
+    for (int t = 0; t < 4; t++) b[0][t] = dequant_word_scaled(stg[0].w[0][t], neg_hi[t], neg_lo[t], delta[t], uc);
+    wait_a(xa[0]);
+
+    int slot = 0;  // ring slot of the stage being consumed
     const int nblk = (stages + D - 1) / D;
     for (int blk = 0; blk < nblk; blk++) {
 #pragma unroll
         for (int d = 0; d < D; d++) {
             const int st = blk * D + d;
-            landed(stg[d], std::integral_constant<int, OX + OW>());
-            asm volatile("s_barrier" ::: "memory");
-            const int fill = slot >= 1 ? slot - 1 : XD - 1;  // (slot + 2) % 3
-            issue_x(fill, sc_(st + 2));
-            issue_w(stg[(d + 2) % D], sc_(st + 2));
-            compute(stg[d], slot, st < stages);
-            slot = slot + 1 == XD ? 0 : slot + 1;
+            Stage &cur_s = stg[d];
+            Stage &next_s = stg[(d + 1) % D];
+            Stage &fill_s = stg[(d + 2) % D];
+            const int slot_next = (slot + 1) & (XD - 1), slot_fill = (slot + 2) & (XD - 1);
+            issue_w(fill_s);
+#pragma unroll
+            for (int ks = 0; ks < 4; ks++) {
+                const int cur = ks & 1, nxt = cur ^ 1;
+                issue_x(slot_fill, 2 * ks);
+                issue_x(slot_fill, 2 * ks + 1);
+                if (ks < 3) {
+                    read_a(xa[nxt], slot, ks + 1);
+                } else {
+                    advance();
+                    landed(next_s, std::integral_constant<int, OX + OW>());
+                    asm volatile("s_barrier" ::: "memory");
+                    stage_consts(next_s, st + 1 < stages);
+                    read_a(xa[nxt], slot_next, 0);
+                }
+                // keep the LDS reads ahead of this k-step's MFMAs and the MFMAs ahead of the
+                // wait: the instruction scheduler would otherwise sink the reads to the wait
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int mt = 0; mt < 4; mt++) {
+                    const h16x8 a = permute_x(xa[cur][mt]);
+#pragma unroll
+                    for (int t = 0; t < 4; t++)
+                        acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b[cur][t], acc[mt][t], 0, 0, 0);
+                    // the next k-step's weight word of column mt, unpacked in the MFMAs' shadow
+                    const uint32_t wnext = ks < 3 ? cur_s.w[ks + 1][mt] : next_s.w[0][mt];
+                    b[nxt][mt] = dequant_word_scaled(wnext, neg_hi[mt], neg_lo[mt], delta[mt], uc);
+                }
+                // issue order inside the k-step: one MFMA, then the vector instructions that
+                // fit in its shadow (4 issue for free per 32x32x16 MFMA)
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // 4 VALU
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                wait_a(xa[nxt]);
+            }
+            slot = slot_next;
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
