@@ -26,12 +26,26 @@
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BM = 256, BK = 64;
 
+#ifdef SQP_PF_CLOCK
+__device__ long long sqp_pf_clk[2];
+#endif
+
+// NT: 32-column MFMA tiles per wave.  NT = 4: the workgroup covers 256 columns (wave tile
+// 128 x 128); NT = 2: 128 columns (wave tile 128 x 64), used for the tiles left over after the
+// last full round of 256-column tiles so that the tail of a launch costs half a round.
+// Workgroup b of the launch handles tile tile0 + b / (4 / NT) of the tn x tm grid of
+// 256 x 256 tiles (column index fastest), column half b % 2 of it when NT = 2.
+template <int NT>
 __global__ void __launch_bounds__(256)
-w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, const uint32_t *__restrict__ packed,
-                        const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y)
+w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h16 *__restrict__ x,
+                     const uint32_t *__restrict__ packed, const h16 *__restrict__ scales,
+                     const uint8_t *__restrict__ zeros, h16 *__restrict__ y)
 {
+    constexpr int WN = 32 * NT;            // columns per wave
+    typedef uint32_t wvec __attribute__((ext_vector_type(NT)));
+    typedef std::conditional_t<NT == 4, u32x2, uint32_t> scvec;
     constexpr int D = 3;                   // register stages of packed weights (two in flight)
     constexpr int XD = 4;                  // LDS slots of activations
     constexpr int XSTAGE = BM * BK * 2;   // 32 KB: 32 blocks of 8 rows x 128 bytes
@@ -43,27 +57,29 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, kb = lane >> 5;
-    const int m0 = blockIdx.y * BM;
-    const int n0 = blockIdx.x * BN + wn * 128;
+    const int tile = tile0 + (int)blockIdx.x / (4 / NT);
+    const int nbase = (tile % tn) * 256 + (NT == 4 ? 0 : ((int)blockIdx.x & 1) * 128);
+    const int m0 = (tile / tn) * BM;
+    const int n0 = nbase + wn * WN;
     const int stages = K / BK;
     const int spg = group / BK;            // stages per quantisation group
 
-    int ncol = n0 + 4 * l32;
+    int ncol = n0 + NT * l32;
     if (ncol >= N) ncol = 0;
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][NT];
 #pragma unroll
     for (int mt = 0; mt < 4; mt++)
 #pragma unroll
-        for (int t = 0; t < 4; t++)
+        for (int t = 0; t < NT; t++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[mt][t][r] = 0.f;
     const UnpackConsts uc = SQP_UNPACK_CONSTS;
 
     struct Stage {
-        u32x4 w[4];   // per k-step: packed words of the lane's 4 columns
-        u32x2 sc;     // 4 fp16 steps
-        uint32_t zr;  // 4 zero points, one byte each
+        wvec w[4];    // per k-step: packed words of the lane's NT columns
+        scvec sc;     // NT fp16 steps
+        uint32_t zr;  // NT zero points, one byte each
     };
 
     // The loading side walks the stages with wave-uniform byte pointers that are advanced by
@@ -78,13 +94,24 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
     const uint32_t voff_w = (uint32_t)(kb * N + ncol) * 4u;
     const uint32_t voff_s = (uint32_t)ncol * 2u, voff_z = (uint32_t)ncol;
     auto issue_w = [&](Stage &s) {
+#ifdef SQP_PF_NOW
+        if (ist > 1) return;
+#endif
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) {
             const unsigned char *base = wq + ks * wrow2;  // wave-uniform
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
+            if constexpr (NT == 4)
+                asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
+            else
+                asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
         }
-        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sq) : "memory");
-        asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zq) : "memory");
+        if constexpr (NT == 4) {
+            asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sq) : "memory");
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zq) : "memory");
+        } else {
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sq) : "memory");
+            asm volatile("global_load_ushort %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zq) : "memory");
+        }
     };
     auto landed = [&](Stage &s, auto after) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(after)::value) : "memory");
@@ -109,6 +136,9 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
         xoff[j] = (uint32_t)grow * (uint32_t)K * 2u + (uint32_t)(piece * 16);
     }
     auto issue_x = [&](int slot, int j) {
+#ifdef SQP_PF_NODMA
+        if (ist > 1) return;
+#endif
         unsigned char *dst = xring + slot * XSTAGE + (wave + 4 * j) * 1024;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xq + xoff[j]),
                                          (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
@@ -130,29 +160,35 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
     const int xkey = (l32 >> 1) & 7;
 
     auto read_a = [&](u32x4 (&xa)[4], int slot, int ks) {
+#ifdef SQP_PF_NOLDS
+        if (ist > 1) return;
+#endif
         const uint32_t poff = xrd0 + (uint32_t)(slot * XSTAGE) + (uint32_t)((((ks * 2 + kb) ^ xkey)) * 16);
 #pragma unroll
         for (int mt = 0; mt < 4; mt++)
             asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(xa[mt]) : "v"(poff), "n"(mt * 4096) : "memory");
     };
     auto wait_a = [&](u32x4 (&xa)[4]) {
+#ifndef SQP_PF_NOLGKM
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#endif
 #pragma unroll
         for (int mt = 0; mt < 4; mt++) asm volatile("" : "+v"(xa[mt]));
     };
 
     // per-stage constants of the unpack: -(1024 + Z), -(64 + Z) and the step, each in both
     // halves of a register; a stage past the end gets a step of 0 and adds nothing
-    h16x2 neg_hi[4], neg_lo[4], delta[4];
+    h16x2 neg_hi[NT], neg_lo[NT], delta[NT];
     auto stage_consts = [&](const Stage &s, bool live) {
         const uint32_t sel_even = live ? 0x01000100u : 0x0c0c0c0cu;  // byte selectors of v_perm_b32
         const uint32_t sel_odd = live ? 0x03020302u : 0x0c0c0c0cu;   // (0x0c selects a zero byte)
 #pragma unroll
-        for (int t = 0; t < 4; t++) {
+        for (int t = 0; t < NT; t++) {
             const uint32_t z = (s.zr >> (8 * t)) & 0xffu;
             neg_hi[t] = neg_hi_of(z);
             neg_lo[t] = neg_lo_of(z);
-            const uint32_t sw = (uint32_t)s.sc[t >> 1];
+            uint32_t sw;
+            if constexpr (NT == 4) sw = s.sc[t >> 1]; else sw = s.sc;
             delta[t] = __builtin_bit_cast(h16x2, __builtin_amdgcn_perm(sw, sw, (t & 1) ? sel_odd : sel_even));
         }
     };
@@ -167,7 +203,7 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
     // loads of stage s+2.
     Stage stg[D];
     u32x4 xa[2][4];
-    h16x8 b[2][4];
+    h16x8 b[2][NT];
     issue_w(stg[0]);
 #pragma unroll
     for (int j = 0; j < OX; j++) issue_x(0, j);
@@ -181,9 +217,12 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
     stage_consts(stg[0], true);
     read_a(xa[0], 0, 0);
 #pragma unroll
-    for (int t = 0; t < 4; t++) b[0][t] = dequant_word_scaled(stg[0].w[0][t], neg_hi[t], neg_lo[t], delta[t], uc);
+    for (int t = 0; t < NT; t++) b[0][t] = dequant_word_scaled(stg[0].w[0][t], neg_hi[t], neg_lo[t], delta[t], uc);
     wait_a(xa[0]);
 
+#ifdef SQP_PF_CLOCK
+    const long long c0 = clock64(), w0 = wall_clock64();
+#endif
     int slot = 0;  // ring slot of the stage being consumed
     const int nblk = (stages + D - 1) / D;
     for (int blk = 0; blk < nblk; blk++) {
@@ -204,8 +243,12 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
                     read_a(xa[nxt], slot, ks + 1);
                 } else {
                     advance();
+#ifndef SQP_PF_NOVMW
                     landed(next_s, std::integral_constant<int, OX + OW>());
+#endif
+#ifndef SQP_PF_NOBAR
                     asm volatile("s_barrier" ::: "memory");
+#endif
                     stage_consts(next_s, st + 1 < stages);
                     read_a(xa[nxt], slot_next, 0);
                 }
@@ -214,27 +257,45 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int mt = 0; mt < 4; mt++) {
+#ifdef SQP_PF_NOPERM
+                    const h16x8 a = __builtin_bit_cast(h16x8, xa[cur][mt]);
+#else
                     const h16x8 a = permute_x(xa[cur][mt]);
+#endif
 #pragma unroll
-                    for (int t = 0; t < 4; t++)
+                    for (int t = 0; t < NT; t++)
                         acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b[cur][t], acc[mt][t], 0, 0, 0);
                     // the next k-step's weight word of column mt, unpacked in the MFMAs' shadow
-                    const uint32_t wnext = ks < 3 ? cur_s.w[ks + 1][mt] : next_s.w[0][mt];
-                    b[nxt][mt] = dequant_word_scaled(wnext, neg_hi[mt], neg_lo[mt], delta[mt], uc);
+                    if (mt < NT) {
+                        const uint32_t wnext = ks < 3 ? cur_s.w[ks + 1][mt] : next_s.w[0][mt];
+#ifdef SQP_PF_NODQ
+                        b[nxt][mt] = __builtin_bit_cast(h16x8, u32x4{wnext, wnext ^ uc.mask_lo, wnext, wnext ^ uc.mask_hi});
+#else
+                        b[nxt][mt] = dequant_word_scaled(wnext, neg_hi[mt], neg_lo[mt], delta[mt], uc);
+#endif
+                    }
                 }
-                // issue order inside the k-step: one MFMA, then the vector instructions that
-                // fit in its shadow (4 issue for free per 32x32x16 MFMA)
+                // issue order inside the k-step: one MFMA, then vector instructions in its
+                // shadow (4 issue for free per 32x32x16 MFMA; the narrow tile has 5.25 per MFMA)
+#ifndef SQP_PF_NOSGB
 #pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // 4 VALU
+                for (int i = 0; i < 4 * NT; i++) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // 1 MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, NT == 4 ? 4 : 5, 0);  // VALU
                 }
+#endif
                 __builtin_amdgcn_sched_barrier(0);
                 wait_a(xa[nxt]);
             }
             slot = slot_next;
         }
     }
+#ifdef SQP_PF_CLOCK
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        sqp_pf_clk[0] = clock64() - c0;
+        sqp_pf_clk[1] = wall_clock64() - w0;
+    }
+#endif
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
     for (int j = 0; j < D; j++) {
@@ -245,12 +306,12 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
     }
 
     // epilogue: accumulator register r of tile (mt, t): row 8*(r/4) + 4*(lane/32) + r%4 of the
-    // 32-row tile, column 4*(lane%32) + t of the wave's 128
+    // 32-row tile, column NT*(lane%32) + t of the wave's 32*NT
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     const int e_l32 = tid & 31, e_kb = (tid >> 5) & 1, e_wave = tid >> 6;
-    const int nout = blockIdx.x * BN + (e_wave & 1) * 128 + 4 * e_l32;
-    const int mrow0 = blockIdx.y * BM + (e_wave >> 1) * 128 + 4 * e_kb;
+    const int nout = nbase + (e_wave & 1) * WN + NT * e_l32;
+    const int mrow0 = m0 + (e_wave >> 1) * 128 + 4 * e_kb;
     if (nout < N) {
         h16 *ycol = y + nout;
 #pragma unroll
@@ -259,23 +320,61 @@ w4a16_prefill_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
             for (int r = 0; r < 16; r++) {
                 const int m = mrow0 + mt * 32 + 8 * (r >> 2) + (r & 3);
                 if (m < M) {
-                    h16x4 o;
-                    o.x = (h16)acc[mt][0][r]; o.y = (h16)acc[mt][1][r];
-                    o.z = (h16)acc[mt][2][r]; o.w = (h16)acc[mt][3][r];
-                    *reinterpret_cast<h16x4 *>(ycol + (size_t)m * N) = o;
+                    if constexpr (NT == 4) {
+                        h16x4 o;
+                        o.x = (h16)acc[mt][0][r]; o.y = (h16)acc[mt][1][r];
+                        o.z = (h16)acc[mt][2][r]; o.w = (h16)acc[mt][3][r];
+                        *reinterpret_cast<h16x4 *>(ycol + (size_t)m * N) = o;
+                    } else {
+                        h16x2 o;
+                        o.x = (h16)acc[mt][0][r]; o.y = (h16)acc[mt][1][r];
+                        *reinterpret_cast<h16x2 *>(ycol + (size_t)m * N) = o;
+                    }
                 }
             }
     }
 }
 
+int compute_units()
+{
+    static int cus = 0;  // same on every device of a node
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
+    }
+    return cus;
+}
+
 }  // namespace
+
+// Test/benchmark hook: 0 = automatic tile choice, 1 = 256-column tiles only, 2 = 128-column
+// tiles only.
+#ifdef SQP_PF_CLOCK
+extern "C" int sqp_debug_prefill_clock(long long *out) { return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(sqp_pf_clk), 16); }
+#endif
+static int g_tile_mode = 0;
+extern "C" void sqp_debug_set_prefill_tiles(int mode) { g_tile_mode = mode; }
 
 int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
                      const h16 *scales, const uint8_t *zeros, h16 *y, hipStream_t stream)
 {
-    if (group % BK == 0 && (M + BM - 1) / BM <= 65535) {
-        dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
-        w4a16_prefill_kernel<<<grid, 256, 0, stream>>>(M, N, K, group, x, packed, scales, zeros, y);
+    if (group % BK == 0) {
+        // One workgroup per compute unit is resident, so a launch proceeds in rounds of `cus`
+        // tiles.  When the last round would be at most half full, its tiles are done as twice
+        // as many half-width tiles by a second launch, which then costs about half a round.
+        const int tn = (N + 255) / 256, tm = (M + BM - 1) / BM;
+        const long tiles = (long)tn * tm;
+        const int cus = compute_units();
+        const long rounds = tiles / cus, left = tiles - rounds * cus;
+        long full = (left > 0 && 2 * left <= cus) ? rounds * cus : tiles;
+        if (g_tile_mode == 1) full = tiles;
+        if (g_tile_mode == 2) full = 0;
+        if (full > 0)
+            w4a16_prefill_kernel<4><<<dim3((unsigned)full), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y);
+        if (full < tiles)
+            w4a16_prefill_kernel<2><<<dim3((unsigned)(2 * (tiles - full))), 256, 0, stream>>>(M, N, K, group, (int)full, tn, x, packed, scales, zeros, y);
         return sqp_launch_status();
     }
     // group sizes the tiled kernel does not cover: the weight-streaming kernel, 64 rows at a time

@@ -132,12 +132,34 @@ def _layer_cached(orc, M, K, N, shape_idx):
 @pytest.mark.parametrize("M,K,N,group", [
     (65, 256, 264, 128), (256, 512, 256, 64), (300, 1024, 520, 128), (130, 384, 72, 64),
     (129, 512, 136, 256), (100, 128, 64, 32), (257, 192, 8, 64), (512, 2048, 1000, 128)])
-def test_prefill_shapes(orc, sqp, M, K, N, group):
+@pytest.mark.parametrize("tiles", [0, 1, 2])
+def test_prefill_shapes(orc, sqp, M, K, N, group, tiles):
     """Tiled matrix-core path: full-output parity on shapes spanning several tiles with
-    ragged edges in M and N, several group sizes (32 takes the fallback path)."""
-    print("case prefill", M, K, N, group, flush=True)
+    ragged edges in M and N, several group sizes (32 takes the fallback path); with the
+    automatic tile choice, with 256-column tiles only and with 128-column tiles only."""
+    print("case prefill", M, K, N, group, tiles, flush=True)
     xs, p, sc, z = _layer(orc, M, K, N, group)
-    _check(orc, sqp, xs, p, sc, z, group)
+    L = sqp.lib()
+    L.sqp_debug_set_prefill_tiles(tiles)
+    try:
+        _check(orc, sqp, xs, p, sc, z, group)
+    finally:
+        L.sqp_debug_set_prefill_tiles(0)
+
+
+def test_prefill_mixed_launch(orc, sqp):
+    """A tile grid of one full round of 256 plus a remainder (N = 4352, M = 3968: 17 x 16 =
+    272 tiles): the automatic choice runs 256 wide tiles and 32 narrow ones.  Sampled rows
+    against the oracle, among them rows of the last row of tiles."""
+    K, N, M = 256, 4352, 3968
+    print("case prefill mixed", M, K, N, flush=True)
+    xs, p, sc, z = _layer(orc, M, K, N, 128)
+    rng = np.random.Generator(np.random.PCG64(21))
+    rows = np.unique(np.concatenate([[0, M - 1, 3839, 3840, 3841], rng.choice(M, 40, replace=False)]))
+    y_ref, t_ref = orc.w4a16_gemm_ref(np.ascontiguousarray(xs[rows]), p, sc, z, 128)
+    y = host(sqp.w4a16_gemm(dev(xs), dev(p), dev(sc), dev(z), 128))
+    ok, worst, nbad = gemm_tolerance_ok(orc, y[rows], y_ref, t_ref)
+    assert ok, "worst err/tol %.3f, %d elements out of tolerance" % (worst, nbad)
 
 
 def test_prefill_integer_exact(orc, sqp):
