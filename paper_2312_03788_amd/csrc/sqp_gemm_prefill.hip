@@ -1,9 +1,9 @@
 // Tiled matrix-core W4A16 GEMM for large M (prefill): y = x * w_hat, Eq. 3 of
 // arXiv 2312.03788 with w_hat = fp16((code - Z) * Delta) of Eq. 1, group-wise along K.
 //
-// A workgroup of 4 waves (one per SIMD, the whole register file each) computes a 256 x 256
-// tile of y; wave (wm, wn) owns 128 rows x 128 columns of it as 4 x 4 accumulator tiles of
-// v_mfma_f32_32x32x16_f16 (256 fp32 registers per lane).
+// A workgroup of W = 4 waves (one per SIMD, the whole register file each) computes a
+// 256 x 256 tile of y; wave (wm, wn) owns 128 rows x 128 columns of it as 4 x 4 accumulator
+// tiles of v_mfma_f32_32x32x16_f16 (256 fp32 registers per lane).
 //   - Weights never pass through LDS: one dwordx4 load per lane fetches, for k-block
 //     (lane / 32), the packed words of 4 adjacent columns; a word is 8 consecutive k of one
 //     column, i.e. one lane's B operand of the 32x32x16 MFMA (column = lane % 32).  The word
@@ -11,14 +11,19 @@
 //     operand feeds 4 MFMAs (the 4 row tiles); each activation fragment feeds 4 as well
 //     (4.25 VALU ops per MFMA).
 //   - Activations are the shared operand: a 256 x 64 slice of x per stage is copied once per
-//     workgroup straight into a three-slot LDS ring (direct global->LDS loads of whole
+//     workgroup straight into a four-slot LDS ring (direct global->LDS loads of whole
 //     128-byte lines, pieces XOR-swizzled so that the 16-byte reads of one k-step spread over
 //     all banks) and every wave reads its A operands from there.
-//   - With a single wave per SIMD nothing else hides latency, so the k-steps are
-//     software-pipelined by hand: while the 16 MFMAs of one k-step run, the activation
-//     fragments of the next are on their way from LDS and the next weight words are unpacked.
+//   - With a single wave per SIMD the order of issue is the schedule, so the MFMAs and the
+//     vector instructions of a k-step are written out in issue order (see the stream below):
+//     while the 16 MFMAs of one k-step run, the activation fragments of the next arrive from
+//     LDS and the next weight words are unpacked; the hand-over to the next stage (wait for
+//     its loads, barrier) sits inside the last k-step, so the pipeline never drains.
 //   - Loads, waits and the per-stage barrier are explicit (assembly), as in the decode
 //     kernel: two stages stay in flight while one is consumed.
+// The same kernel with W = 8 waves of 128 x 64 (two per SIMD) needs fewer cycles per MFMA but
+// the chip then clocks lower under its power limit and the result was a little slower, so the
+// four-wave shape is the one launched.
 #include <type_traits>
 
 #include "sqp_common.h"
@@ -28,17 +33,14 @@ namespace {
 
 constexpr int BM = 256, BK = 64;
 
-#ifdef SQP_PF_CLOCK
-__device__ long long sqp_pf_clk[2];
-#endif
-
-// NT: 32-column MFMA tiles per wave.  NT = 4: the workgroup covers 256 columns (wave tile
-// 128 x 128); NT = 2: 128 columns (wave tile 128 x 64), used for the tiles left over after the
-// last full round of 256-column tiles so that the tail of a launch costs half a round.
-// Workgroup b of the launch handles tile tile0 + b / (4 / NT) of the tn x tm grid of
-// 256 x 256 tiles (column index fastest), column half b % 2 of it when NT = 2.
-template <int NT>
-__global__ void __launch_bounds__(256)
+// NT: 32-column MFMA tiles per wave; W: waves, arranged 2 (rows) x W/2 (columns).
+// <4, 4>: the workgroup covers 256 columns (wave tile 128 x 128).  <2, 4>: 128 columns (wave
+// tile 128 x 64), used for the tiles left over after the last full round of 256-column tiles
+// so that the tail of a launch costs half a round.  <2, 8>: 256 columns with two waves per SIMD.
+// Workgroup b of the launch handles tile tile0 + b / (256 / columns) of the tn x tm grid of
+// 256 x 256 tiles (column index fastest), column half b % 2 of it when it covers 128.
+template <int NT, int W>
+__global__ void __launch_bounds__(W * 64)
 w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h16 *__restrict__ x,
                      const uint32_t *__restrict__ packed, const h16 *__restrict__ scales,
                      const uint8_t *__restrict__ zeros, h16 *__restrict__ y)
@@ -49,16 +51,17 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     constexpr int D = 3;                   // register stages of packed weights (two in flight)
     constexpr int XD = 4;                  // LDS slots of activations
     constexpr int XSTAGE = BM * BK * 2;   // 32 KB: 32 blocks of 8 rows x 128 bytes
-    constexpr int OX = 8;                  // direct loads per wave per stage (32 blocks / 4 waves)
+    constexpr int OX = 32 / W;             // direct loads per wave per stage (32 blocks of 1 KB)
+    constexpr int WGN = (W / 2) * WN;      // columns per workgroup: 256 or 128
     constexpr int OW = 4 + 2;
     __shared__ __attribute__((aligned(1024))) unsigned char xring[XD * XSTAGE];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / (W / 2), wn = wave % (W / 2);
     const int l32 = lane & 31, kb = lane >> 5;
-    const int tile = tile0 + (int)blockIdx.x / (4 / NT);
-    const int nbase = (tile % tn) * 256 + (NT == 4 ? 0 : ((int)blockIdx.x & 1) * 128);
+    const int tile = tile0 + (int)blockIdx.x / (256 / WGN);
+    const int nbase = (tile % tn) * 256 + (WGN == 256 ? 0 : ((int)blockIdx.x & 1) * 128);
     const int m0 = (tile / tn) * BM;
     const int n0 = nbase + wn * WN;
     const int stages = K / BK;
@@ -94,9 +97,6 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     const uint32_t voff_w = (uint32_t)(kb * N + ncol) * 4u;
     const uint32_t voff_s = (uint32_t)ncol * 2u, voff_z = (uint32_t)ncol;
     auto issue_w = [&](Stage &s) {
-#ifdef SQP_PF_NOW
-        if (ist > 1) return;
-#endif
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) {
             const unsigned char *base = wq + ks * wrow2;  // wave-uniform
@@ -128,7 +128,7 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     uint32_t xoff[OX];
 #pragma unroll
     for (int j = 0; j < OX; j++) {
-        const int b = wave + 4 * j;
+        const int b = wave + W * j;
         const int row = b * 8 + (lane >> 3);
         int grow = m0 + row;
         if (grow >= M) grow = M - 1;
@@ -136,10 +136,7 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
         xoff[j] = (uint32_t)grow * (uint32_t)K * 2u + (uint32_t)(piece * 16);
     }
     auto issue_x = [&](int slot, int j) {
-#ifdef SQP_PF_NODMA
-        if (ist > 1) return;
-#endif
-        unsigned char *dst = xring + slot * XSTAGE + (wave + 4 * j) * 1024;
+        unsigned char *dst = xring + slot * XSTAGE + (wave + W * j) * 1024;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xq + xoff[j]),
                                          (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     };
@@ -160,18 +157,13 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     const int xkey = (l32 >> 1) & 7;
 
     auto read_a = [&](u32x4 (&xa)[4], int slot, int ks) {
-#ifdef SQP_PF_NOLDS
-        if (ist > 1) return;
-#endif
         const uint32_t poff = xrd0 + (uint32_t)(slot * XSTAGE) + (uint32_t)((((ks * 2 + kb) ^ xkey)) * 16);
 #pragma unroll
         for (int mt = 0; mt < 4; mt++)
             asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(xa[mt]) : "v"(poff), "n"(mt * 4096) : "memory");
     };
     auto wait_a = [&](u32x4 (&xa)[4]) {
-#ifndef SQP_PF_NOLGKM
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#endif
 #pragma unroll
         for (int mt = 0; mt < 4; mt++) asm volatile("" : "+v"(xa[mt]));
     };
@@ -202,8 +194,70 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     // (four slots) and weight registers (three stages) are refilled during stage s with the
     // loads of stage s+2.
     Stage stg[D];
-    u32x4 xa[2][4];
-    h16x8 b[2][NT];
+    u32x4 xa[2][4];          // raw A fragments from LDS: [k-step parity][row tile]
+    uint32_t aq[2][4];       // permuted A operand of row tile m in aq[m % 2]
+    uint32_t bq[2][NT][4];   // B operands (dequantised weights): [k-step parity][column tile]
+    uint32_t w8[NT];
+    const uint32_t sel_a = 0x05040100u, sel_b = 0x07060302u;  // v_perm_b32 selectors of permute_x
+
+    // ---- The instruction stream of one k-step, in issue order, written out by hand.
+    // With one wave per SIMD the order of issue is the schedule: measured on this chip, an
+    // independent vector instruction costs 4 cycles and up to 4 of them hide behind a
+    // 32x32x16 MFMA, but one that depends on the instruction just before it costs about 8, and
+    // the compiler's own order left many such pairs.  So every MFMA and every vector
+    // instruction of the k-step is a volatile asm statement (these keep their order), grouped
+    // so that a result is used no sooner than 4 instructions later:
+    //   MFMA i (row tile i / NT, column tile i % NT), then the next 4-5 entries of the list
+    //     P1, S, AO.., P2, AO.., ADD.., P3, ADD.., MUL.., P0', MUL
+    //   P<m>: 4 perms giving row tile m's A operand (P0': row tile 0 of the NEXT k-step, after
+    //   the wait for its LDS reads); S: word >> 8; AO/ADD/MUL<t>: the and-or, add and multiply
+    //   of the 4 registers of the next k-step's B operand t.
+    // The compiler does not look inside asm statements, so the wait states it would insert
+    // are guaranteed by the order itself: vector write -> MFMA read needs 2 (every operand is
+    // written >= 4 instructions ahead), vector write -> packed-math read needs 1.
+    auto mfma = [&](f32x16 &c, const uint32_t (&av)[4], const uint32_t (&bv)[4]) {
+        const u32x4 a4 = {av[0], av[1], av[2], av[3]};
+        const u32x4 b4 = {bv[0], bv[1], bv[2], bv[3]};
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a4), "v"(b4));
+    };
+    auto perm4 = [&](uint32_t (&dst)[4], const u32x4 &v, int j) {
+        if (j == 0) asm volatile("v_perm_b32 %0, %1, %2, %3" : "=v"(dst[0]) : "v"(v.z), "v"(v.x), "s"(sel_a));
+        if (j == 1) asm volatile("v_perm_b32 %0, %1, %2, %3" : "=v"(dst[1]) : "v"(v.z), "v"(v.x), "s"(sel_b));
+        if (j == 2) asm volatile("v_perm_b32 %0, %1, %2, %3" : "=v"(dst[2]) : "v"(v.w), "v"(v.y), "s"(sel_a));
+        if (j == 3) asm volatile("v_perm_b32 %0, %1, %2, %3" : "=v"(dst[3]) : "v"(v.w), "v"(v.y), "s"(sel_b));
+    };
+    enum { G_P1, G_P2, G_P3, G_P0N, G_S, G_AO, G_ADD = G_AO + 4, G_MUL = G_ADD + 4 };
+    constexpr int NG = NT == 4 ? 17 : 11;
+    constexpr int order4[17] = {G_P1, G_S, G_AO + 0, G_AO + 1, G_P2, G_AO + 2, G_AO + 3, G_ADD + 0, G_P3,
+                                G_ADD + 1, G_ADD + 2, G_ADD + 3, G_MUL + 0, G_MUL + 1, G_MUL + 2, G_P0N, G_MUL + 3};
+    constexpr int order2[17] = {G_P1, G_S, G_P2, G_AO + 0, G_AO + 1, G_P3, G_ADD + 0, G_ADD + 1, G_MUL + 0, G_P0N, G_MUL + 1,
+                                0, 0, 0, 0, 0, 0};
+    constexpr int NMF = 4 * NT;                 // MFMAs per k-step
+    constexpr int WAIT_AT = NT == 4 ? 13 : 5;   // the LDS wait goes in front of this MFMA
+
+    // one entry j of group g; wn = the packed words of the next k-step
+    auto valu = [&](int g, int j, int cur, const wvec &wn) {
+        const int nxt = cur ^ 1;
+        if (g == G_P1) perm4(aq[1], xa[cur][1], j);
+        else if (g == G_P2) perm4(aq[0], xa[cur][2], j);
+        else if (g == G_P3) perm4(aq[1], xa[cur][3], j);
+        else if (g == G_P0N) perm4(aq[0], xa[nxt][0], j);
+        else if (g == G_S) {
+            if (j < NT) asm volatile("v_lshrrev_b32 %0, 8, %1" : "=v"(w8[j]) : "v"(wn[j]));
+        } else if (g < G_ADD) {
+            const int t = g - G_AO;
+            if (j & 1) asm volatile("v_and_or_b32 %0, %1, %2, %3" : "=v"(bq[nxt][t][j]) : "v"(j < 2 ? wn[t] : w8[t]), "v"(uc.mask_hi), "v"(uc.magic_hi));
+            else       asm volatile("v_and_or_b32 %0, %1, %2, %3" : "=v"(bq[nxt][t][j]) : "v"(j < 2 ? wn[t] : w8[t]), "v"(uc.mask_lo), "v"(uc.magic_lo));
+        } else if (g < G_MUL) {
+            const int t = g - G_ADD;
+            if (j & 1) asm volatile("v_pk_add_f16 %0, %0, %1" : "+v"(bq[nxt][t][j]) : "v"(neg_lo[t]));
+            else       asm volatile("v_pk_add_f16 %0, %0, %1" : "+v"(bq[nxt][t][j]) : "v"(neg_hi[t]));
+        } else {
+            const int t = g - G_MUL;
+            asm volatile("v_pk_mul_f16 %0, %0, %1" : "+v"(bq[nxt][t][j]) : "v"(delta[t]));
+        }
+    };
+
     issue_w(stg[0]);
 #pragma unroll
     for (int j = 0; j < OX; j++) issue_x(0, j);
@@ -216,13 +270,19 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     asm volatile("s_barrier" ::: "memory");
     stage_consts(stg[0], true);
     read_a(xa[0], 0, 0);
+    // first operands of the pipeline, by the ordinary helpers
 #pragma unroll
-    for (int t = 0; t < NT; t++) b[0][t] = dequant_word_scaled(stg[0].w[0][t], neg_hi[t], neg_lo[t], delta[t], uc);
+    for (int t = 0; t < NT; t++) {
+        const u32x4 bw = __builtin_bit_cast(u32x4, dequant_word_scaled(stg[0].w[0][t], neg_hi[t], neg_lo[t], delta[t], uc));
+        bq[0][t][0] = bw.x; bq[0][t][1] = bw.y; bq[0][t][2] = bw.z; bq[0][t][3] = bw.w;
+    }
     wait_a(xa[0]);
+    {
+        const u32x4 a0 = __builtin_bit_cast(u32x4, permute_x(xa[0][0]));
+        aq[0][0] = a0.x; aq[0][1] = a0.y; aq[0][2] = a0.z; aq[0][3] = a0.w;
+    }
+    asm volatile("s_nop 3" ::: "memory");  // compiler-issued vector writes above -> asm MFMA reads below
 
-#ifdef SQP_PF_CLOCK
-    const long long c0 = clock64(), w0 = wall_clock64();
-#endif
     int slot = 0;  // ring slot of the stage being consumed
     const int nblk = (stages + D - 1) / D;
     for (int blk = 0; blk < nblk; blk++) {
@@ -237,72 +297,47 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
 #pragma unroll
             for (int ks = 0; ks < 4; ks++) {
                 const int cur = ks & 1, nxt = cur ^ 1;
-                issue_x(slot_fill, 2 * ks);
-                issue_x(slot_fill, 2 * ks + 1);
+#pragma unroll
+                for (int j = 0; j < OX / 4; j++) issue_x(slot_fill, (OX / 4) * ks + j);
                 if (ks < 3) {
                     read_a(xa[nxt], slot, ks + 1);
                 } else {
                     advance();
-#ifndef SQP_PF_NOVMW
                     landed(next_s, std::integral_constant<int, OX + OW>());
-#endif
-#ifndef SQP_PF_NOBAR
                     asm volatile("s_barrier" ::: "memory");
-#endif
                     stage_consts(next_s, st + 1 < stages);
                     read_a(xa[nxt], slot_next, 0);
                 }
-                // keep the LDS reads ahead of this k-step's MFMAs and the MFMAs ahead of the
-                // wait: the instruction scheduler would otherwise sink the reads to the wait
-                __builtin_amdgcn_sched_barrier(0);
+                const wvec wn = ks < 3 ? cur_s.w[ks + 1] : next_s.w[0];
 #pragma unroll
-                for (int mt = 0; mt < 4; mt++) {
-#ifdef SQP_PF_NOPERM
-                    const h16x8 a = __builtin_bit_cast(h16x8, xa[cur][mt]);
-#else
-                    const h16x8 a = permute_x(xa[cur][mt]);
-#endif
+                for (int i = 0; i < NMF; i++) {
+                    if (i == WAIT_AT) wait_a(xa[nxt]);
+                    mfma(acc[i / NT][i % NT], aq[(i / NT) & 1], bq[cur][i % NT]);
 #pragma unroll
-                    for (int t = 0; t < NT; t++)
-                        acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b[cur][t], acc[mt][t], 0, 0, 0);
-                    // the next k-step's weight word of column mt, unpacked in the MFMAs' shadow
-                    if (mt < NT) {
-                        const uint32_t wnext = ks < 3 ? cur_s.w[ks + 1][mt] : next_s.w[0][mt];
-#ifdef SQP_PF_NODQ
-                        b[nxt][mt] = __builtin_bit_cast(h16x8, u32x4{wnext, wnext ^ uc.mask_lo, wnext, wnext ^ uc.mask_hi});
-#else
-                        b[nxt][mt] = dequant_word_scaled(wnext, neg_hi[mt], neg_lo[mt], delta[mt], uc);
-#endif
-                    }
+                    for (int e = i * (4 * NG) / NMF; e < (i + 1) * (4 * NG) / NMF; e++)
+                        valu(NT == 4 ? order4[e / 4] : order2[e / 4], e % 4, cur, wn);
                 }
-                // issue order inside the k-step: one MFMA, then vector instructions in its
-                // shadow (4 issue for free per 32x32x16 MFMA; the narrow tile has 5.25 per MFMA)
-#ifndef SQP_PF_NOSGB
+            }
+            // End of the last iteration.  (1) Drain the clamped look-ahead loads: their
+            // destination registers are dead as far as the compiler can tell, but the hardware
+            // still writes them when the data arrives, so the empty uses keep every stage
+            // allocated until the wait has completed.  (2) The compiler does not know that the
+            // asm statements above wrote the accumulators with MFMAs, so it will not insert the
+            // wait states a matrix result needs before another instruction may read it (up to
+            // 18); the epilogue's reads follow the loop directly, so they are spent here.
+            if (d == D - 1 && blk == nblk - 1) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-                for (int i = 0; i < 4 * NT; i++) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // 1 MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x002, NT == 4 ? 4 : 5, 0);  // VALU
+                for (int j = 0; j < D; j++) {
+#pragma unroll
+                    for (int ks = 0; ks < 4; ks++) asm volatile("" ::"v"(stg[j].w[ks]));
+                    asm volatile("" ::"v"(stg[j].sc));
+                    asm volatile("" ::"v"(stg[j].zr));
                 }
-#endif
-                __builtin_amdgcn_sched_barrier(0);
-                wait_a(xa[nxt]);
+                asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
             }
             slot = slot_next;
         }
-    }
-#ifdef SQP_PF_CLOCK
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        sqp_pf_clk[0] = clock64() - c0;
-        sqp_pf_clk[1] = wall_clock64() - w0;
-    }
-#endif
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-    for (int j = 0; j < D; j++) {
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) asm volatile("" ::"v"(stg[j].w[ks]));
-        asm volatile("" ::"v"(stg[j].sc));
-        asm volatile("" ::"v"(stg[j].zr));
     }
 
     // epilogue: accumulator register r of tile (mt, t): row 8*(r/4) + 4*(lane/32) + r%4 of the
@@ -310,8 +345,8 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     const int e_l32 = tid & 31, e_kb = (tid >> 5) & 1, e_wave = tid >> 6;
-    const int nout = nbase + (e_wave & 1) * WN + NT * e_l32;
-    const int mrow0 = m0 + (e_wave >> 1) * 128 + 4 * e_kb;
+    const int nout = nbase + (e_wave % (W / 2)) * WN + NT * e_l32;
+    const int mrow0 = m0 + (e_wave / (W / 2)) * 128 + 4 * e_kb;
     if (nout < N) {
         h16 *ycol = y + nout;
 #pragma unroll
@@ -349,11 +384,13 @@ int compute_units()
 
 }  // namespace
 
+#ifndef SQP_PF_MAIN_W
+#define SQP_PF_MAIN_W 4
+#endif
+constexpr int MAIN_W = SQP_PF_MAIN_W, MAIN_NT = MAIN_W == 8 ? 2 : 4;
+
 // Test/benchmark hook: 0 = automatic tile choice, 1 = 256-column tiles only, 2 = 128-column
 // tiles only.
-#ifdef SQP_PF_CLOCK
-extern "C" int sqp_debug_prefill_clock(long long *out) { return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(sqp_pf_clk), 16); }
-#endif
 static int g_tile_mode = 0;
 extern "C" void sqp_debug_set_prefill_tiles(int mode) { g_tile_mode = mode; }
 
@@ -372,9 +409,9 @@ int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_
         if (g_tile_mode == 1) full = tiles;
         if (g_tile_mode == 2) full = 0;
         if (full > 0)
-            w4a16_prefill_kernel<4><<<dim3((unsigned)full), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y);
+            w4a16_prefill_kernel<MAIN_NT, MAIN_W><<<dim3((unsigned)full), MAIN_W * 64, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y);
         if (full < tiles)
-            w4a16_prefill_kernel<2><<<dim3((unsigned)(2 * (tiles - full))), 256, 0, stream>>>(M, N, K, group, (int)full, tn, x, packed, scales, zeros, y);
+            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)(2 * (tiles - full))), 256, 0, stream>>>(M, N, K, group, (int)full, tn, x, packed, scales, zeros, y);
         return sqp_launch_status();
     }
     // group sizes the tiled kernel does not cover: the weight-streaming kernel, 64 rows at a time
