@@ -154,7 +154,8 @@ def main():
     bytes_per_launch = bytes_per_step / launches_per_step
     achieved = bytes_per_launch / avg_launch_s / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": TRAFFIC_BYTES_PER_LAUNCH if (args.model == "34b" and M == 16) else None,
                 "kernel": "w4a16_decode_kernel", "avg_launch_us": round(avg_launch_s * 1e6, 2),
                 "algorithmic_bytes_per_launch": round(bytes_per_launch)}
 
@@ -235,6 +236,22 @@ def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, 
     extra["prefill_m2048_tflops_by_shape"] = pre
     extra["prefill_m2048_tflops"] = round(flops_total / t_total / 1e12, 1)
     extra["prefill_m2048_pct_mfma_peak"] = round(100 * flops_total / t_total / 1e12 / MFMA_F16_PEAK_TFLOPS, 2)
+    # what the matrix cores sustain on this chip with nothing else to do: a loop of independent
+    # 32x32x16 fp16 MFMAs on one of the activations above (the clock settles under the power limit)
+    import ctypes
+    L = sqp.lib()
+    L.sqp_debug_mfma_ceiling.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    data = sqp.smooth_apply_x(activation(16, shapes[0][0], 2016), s_first[0])  # >= 64 KiB of smoothed activations
+    blocks, iters = 256, 20000
+    sink = torch.empty(blocks * 256, device=dev, dtype=torch.float32)
+    st = torch.cuda.current_stream().cuda_stream
+
+    def mf():
+        rc = L.sqp_debug_mfma_ceiling(data.data_ptr(), sink.data_ptr(), blocks, iters, st)
+        assert rc == 0
+    t = _time(torch, mf, 3)
+    extra["mfma_only_loop_tflops"] = round(blocks * 4 * iters * 16 * 32768.0 / t / 1e12, 1)
+    del data, sink
     # companion kernels on the largest weight (22016 x 8192)
     K, N = shapes[3]
     gen = torch.Generator(device=dev)

@@ -32,6 +32,49 @@ extern "C" int sqp_debug_plain_copy(const void *src, void *dst, size_t bytes, vo
     return sqp_launch_status();
 }
 
+// A loop of nothing but independent 32x32x16 fp16 MFMAs (16 accumulator tiles per wave, four
+// waves per workgroup, operands taken from `data`): the rate the matrix cores sustain on this
+// chip for the given operand values, i.e. the ceiling the tiled GEMM is measured against
+// beside the published peak.  Benchmark hook, not part of the ABI.
+__global__ void __launch_bounds__(256) mfma_ceiling_kernel(const h16x8 *__restrict__ data, float *__restrict__ out, int iters)
+{
+    h16x8 a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        a[i] = data[(threadIdx.x + 256 * i) & 4095];
+        b[i] = data[(threadIdx.x + 256 * (i + 4)) & 4095];
+    }
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) sum += acc[i][j][r];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = sum;
+}
+// data: 64 KiB of fp16 values on the device; out: blocks * 256 floats.  Flops of the launch:
+// blocks * 4 waves * iters * 16 MFMAs * 32768.
+extern "C" int sqp_debug_mfma_ceiling(const void *data, float *out, int blocks, int iters, void *stream)
+{
+    if (!data || !out || blocks <= 0 || iters <= 0) return SQP_ERR_ARG;
+    mfma_ceiling_kernel<<<blocks, 256, 0, (hipStream_t)stream>>>((const h16x8 *)data, out, iters);
+    return sqp_launch_status();
+}
+
 static int g_decode_max_m = 64;
 // Test/benchmark hook: rows up to which the weight-streaming path is used.
 extern "C" void sqp_debug_set_decode_max_m(int m) { g_decode_max_m = m; }

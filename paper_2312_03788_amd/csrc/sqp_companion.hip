@@ -153,8 +153,26 @@ __device__ __forceinline__ uint32_t code_of(float v, const GroupParams &p)
     return (uint32_t)q;
 }
 
+// The code of Eq. 1 needs rint(v / d) with the correctly rounded quotient.  A full IEEE
+// division per weight makes the kernel ALU-bound, so the quotient is first formed as
+// t = v * (1 / d): |t - v/d| <= 2^-23 * |v/d| <= 1.8e-6 (|v/d| <= 15.01 because the group's
+// range contains 0), and the rounded quotient lies within 0.9e-6 of v/d.  Unless t is within
+// NEAR_TIE of a half-integer, rint(t) is therefore rint of the exact quotient; the rare
+// words with such a value are redone with the division (a wave-uniform branch).
+constexpr float NEAR_TIE = 4.0e-6f;
+
+__device__ __forceinline__ uint32_t code_fast(float v, float inv, int z, bool &near_tie)
+{
+    const float t = v * inv;
+    const float r = rintf(t);
+    near_tie |= fabsf(t - r) >= 0.5f - NEAR_TIE;
+    int q = (int)r + z;
+    q = q < 0 ? 0 : (q > 15 ? 15 : q);
+    return (uint32_t)q;
+}
+
 // One thread quantises one group of G rows of two adjacent columns; the 2*G weights
-// stay in registers between the min/max pass and the coding pass.
+// stay in registers between the min/max pass (exact packed fp16 min/max) and the coding pass.
 // grid: (ceil(N/512), K/G), block 256.
 template <int G>
 __global__ void __launch_bounds__(256) quantize_pack_reg_kernel(int N, const uint32_t *w, uint2 *packed, uint32_t *scales, uint16_t *zeros)
@@ -167,26 +185,35 @@ __global__ void __launch_bounds__(256) quantize_pack_reg_kernel(int N, const uin
     uint32_t v[G];
 #pragma unroll
     for (int i = 0; i < G; i++) v[i] = wp[(size_t)i * N2];
-    float mn0 = h2f_lo(v[0]), mx0 = mn0, mn1 = h2f_hi(v[0]), mx1 = mn1;
+    h16x2 mn = __builtin_bit_cast(h16x2, v[0]), mx = mn;
 #pragma unroll
     for (int i = 1; i < G; i++) {
-        float a = h2f_lo(v[i]), b = h2f_hi(v[i]);
-        mn0 = fminf(mn0, a);
-        mx0 = fmaxf(mx0, a);
-        mn1 = fminf(mn1, b);
-        mx1 = fmaxf(mx1, b);
+        const h16x2 c = __builtin_bit_cast(h16x2, v[i]);
+        mn = __builtin_elementwise_min(mn, c);
+        mx = __builtin_elementwise_max(mx, c);
     }
-    GroupParams p0 = group_params(mn0, mx0), p1 = group_params(mn1, mx1);
+    const GroupParams p0 = group_params((float)mn.x, (float)mx.x), p1 = group_params((float)mn.y, (float)mx.y);
     scales[(size_t)t * N2 + n2] = (uint32_t)p0.d16 | ((uint32_t)p1.d16 << 16);
     zeros[(size_t)t * N2 + n2] = (uint16_t)(p0.z | (p1.z << 8));
+    const float inv0 = 1.0f / p0.d, inv1 = 1.0f / p1.d;
     uint2 *pp = packed + (size_t)t * (G / 8) * N2 + n2;
 #pragma unroll
     for (int j = 0; j < G / 8; j++) {
         uint32_t w0 = 0, w1 = 0;
+        bool near_tie = false;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            w0 |= code_of(h2f_lo(v[8 * j + i]), p0) << (4 * i);
-            w1 |= code_of(h2f_hi(v[8 * j + i]), p1) << (4 * i);
+            w0 |= code_fast(h2f_lo(v[8 * j + i]), inv0, p0.z, near_tie) << (4 * i);
+            w1 |= code_fast(h2f_hi(v[8 * j + i]), inv1, p1.z, near_tie) << (4 * i);
+        }
+        if (__builtin_amdgcn_ballot_w64(near_tie) != 0ull) {
+            w0 = 0;
+            w1 = 0;
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                w0 |= code_of(h2f_lo(v[8 * j + i]), p0) << (4 * i);
+                w1 |= code_of(h2f_hi(v[8 * j + i]), p1) << (4 * i);
+            }
         }
         pp[(size_t)j * N2] = make_uint2(w0, w1);
     }
