@@ -98,13 +98,8 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // 32-bit offset that never changes, so the loads cost no vector arithmetic.  The loads are
     // written in assembly so that this kernel, not the compiler, decides when to wait for
     // them: a stage must not be read before `landed` below.
-#ifdef SQP_PROBE_TILED
-    const uint32_t voff_w = (uint32_t)(lk * 64 + (ncol & 63)) * 4u + (uint32_t)(ncol >> 6) * (uint32_t)(K / 8) * 256u;
-    const int wrow_stride = 64;
-#else
     const uint32_t voff_w = (uint32_t)(lk * N + ncol) * 4u;
     const int wrow_stride = N;
-#endif
     const uint32_t voff_s = (uint32_t)ncol * 2u, voff_z = (uint32_t)ncol;
     auto issue_w = [&](Stage &s, int g) {
 #pragma unroll
@@ -163,16 +158,6 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     const int xsw = lc % PP;  // the row's swizzle (16 % PP == 0, so mt does not matter)
 
     auto compute = [&](const Stage &s, int slot, bool live) {
-#ifdef SQP_PROBE_NOCOMPUTE
-        {
-            uint32_t h = s.zr ^ s.sc[0] ^ s.sc[1];
-#pragma unroll
-            for (int ks = 0; ks < KSPG; ks++) h ^= s.w[ks][0] ^ s.w[ks][1] ^ s.w[ks][2] ^ s.w[ks][3];
-            acc[0][0][0] += live ? __builtin_bit_cast(float, h & 0x3fffffffu) : 0.f;
-            (void)slot;
-            return;
-        }
-#endif
         f32x4 accg[MT][4];
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
@@ -422,7 +407,6 @@ int get_workspace(Workspace *out, hipStream_t st)
     return SQP_OK;
 }
 
-static int g_dyn_lds = 0;  // benchmark hook: extra LDS per workgroup (limits workgroups per compute unit)
 
 template <int MT, int NW, int KSPG>
 int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t *packed, const h16 *scales,
@@ -442,7 +426,7 @@ int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t
         int rc = get_workspace(&ws, st);
         if (rc) return rc;
     }
-    w4a16_decode_kernel<MT, NW, KSPG><<<dim3(tiles, split), NW * 64, g_dyn_lds, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws);
+    w4a16_decode_kernel<MT, NW, KSPG><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws);
     return sqp_launch_status();
 }
 
@@ -498,7 +482,6 @@ int dispatch_kspg(const Plan &p, int M, int N, int K, int cpg, const h16 *x, con
 static int g_force_split = 0;
 static Plan g_force_plan = {0, 0};
 extern "C" void sqp_debug_set_decode_split(int split) { g_force_split = split; }
-extern "C" void sqp_debug_set_decode_dyn_lds(int bytes) { g_dyn_lds = bytes; }
 extern "C" void sqp_debug_set_decode_plan(int nw, int split) { g_force_plan = Plan{nw, split}; }
 
 int sqp_gemm_generic(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
