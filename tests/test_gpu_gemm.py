@@ -110,6 +110,16 @@ def test_cfg2_7b_shapes(orc, sqp, shape_idx, M):
     _check(orc, sqp, xs, p, sc, z, 128)
 
 
+@pytest.mark.parametrize("shape_idx", [0, 1, 2, 3])
+def test_cfg4_34b_decode_shapes(orc, sqp, shape_idx):
+    """The four Code Llama-34B layer shapes at M = 16 with the library's own launch plan:
+    the configuration the benchmark times.  Full-output parity against the oracle."""
+    K, N = wl.MODEL_SHAPES["34b"][shape_idx]
+    print("case 34b", K, N, 16, flush=True)
+    xs, p, sc, z = _layer_cached(orc, 16, K, N, shape_idx)
+    _check(orc, sqp, xs, p, sc, z, 128)
+
+
 _cache = {}
 
 
