@@ -266,6 +266,24 @@ def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, 
     t = _time(torch, lambda: sqp.quantize_pack(w, G, out=out), 5)
     extra["quantize_pack_22016x8192_us"] = round(t * 1e6, 1)
     extra["quantize_pack_gbs"] = round((2.0 * K * N + K * N * (0.5 + 3.0 / G)) / t / 1e9, 1)
+    # single-layer search for the smoothing strength (Eq. 4 over 21 values of alpha) on the
+    # 8192 -> 8192 linear with the 512 calibration rows
+    K2, N2 = shapes[1]
+    w2 = (torch.randn((K2, N2), device=dev, generator=gen, dtype=torch.float32) * 0.02).half()
+    xcal2 = activation(wl.T_CAL, K2, 3000)
+    s2 = torch.empty(K2, device=dev, dtype=torch.float32)
+    sqp.smooth_scales(xcal2, w2, wl.ALPHA, out=s2)
+    xh2 = sqp.smooth_apply_x(xcal2, s2)
+    q2 = sqp.quantize_pack(sqp.smooth_apply_w(w2, s2), G)
+    lo = torch.empty(1, device=dev, dtype=torch.float64)
+    t = _time(torch, lambda: sqp.quant_loss(xcal2, w2, xh2, q2[0], q2[1], q2[2], G, out=lo), 5)
+    extra["quant_loss_%dx%dx%d_us" % (wl.T_CAL, K2, N2)] = round(t * 1e6, 1)
+    extra["quant_loss_tflops"] = round(4.0 * wl.T_CAL * K2 * N2 / t / 1e12, 1)
+    t0 = time.time()
+    best, curve = sqp.alpha_search(xcal2, w2, G)
+    torch.cuda.synchronize()
+    extra["alpha_search_21_ms"] = round((time.time() - t0) * 1e3, 1)
+    extra["alpha_search_best"] = round(best, 2)
     return extra
 
 

@@ -90,6 +90,21 @@ int sqp_dequantize(int N, int K, int group, const uint32_t *packed, const void *
 int sqp_w4a16_gemm(int M, int N, int K, int group, const void *x, const uint32_t *packed,
                    const void *scales, const uint8_t *zeros, void *y, void *stream);
 
+/* Quantisation loss of one layer, Eq. 4:  *loss = || x w - x_hat w_hat ||_F^2  with
+ * w_hat the dequantised weights of (packed, scales, zeros) (Eq. 1) - the quantity the search
+ * over the smoothing strength alpha minimises (Sec 2.2, Eq. 6), for one layer.  Both products
+ * are accumulated together in fp32 (the difference is formed before any rounding to fp16),
+ * the squares are summed in fp64 in a fixed order (run-to-run deterministic).
+ *   x     [M][K] fp16  calibration activations        w [K][N] fp16  the unsmoothed weight
+ *   x_hat [M][K] fp16  smoothed activations (Eq. 5)   packed/scales/zeros: quantised smoothed weight
+ *   scratch  device, at least sqp_quant_loss_scratch_doubles(M, N) doubles, overwritten
+ *   loss     device, one double (out)
+ * All device pointers; nothing is allocated. */
+long sqp_quant_loss_scratch_doubles(int M, int N);
+int sqp_quant_loss(int M, int N, int K, int group, const void *x, const void *w, const void *x_hat,
+                   const uint32_t *packed, const void *scales, const uint8_t *zeros, double *scratch,
+                   double *loss, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

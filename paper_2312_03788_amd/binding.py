@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("SQP_LIBRARY", os.path.join(_HERE, "libsqp.so"))  # override: another build
 
 EXPORTS = ["sqp_status_string", "sqp_smooth_scales", "sqp_smooth_apply_x", "sqp_smooth_apply_w",
-           "sqp_quantize_pack", "sqp_dequantize", "sqp_w4a16_gemm"]
+           "sqp_quantize_pack", "sqp_dequantize", "sqp_w4a16_gemm", "sqp_quant_loss"]
 
 
 class SqpError(RuntimeError):
@@ -39,8 +39,11 @@ def lib():
         L.sqp_quantize_pack.argtypes = [i, i, i, vp, vp, vp, vp, vp]
         L.sqp_dequantize.argtypes = [i, i, i, vp, vp, vp, vp, vp]
         L.sqp_w4a16_gemm.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp]
+        L.sqp_quant_loss.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.sqp_quant_loss_scratch_doubles.argtypes = [i, i]
         for name in EXPORTS[1:]:
             getattr(L, name).restype = ctypes.c_int
+        L.sqp_quant_loss_scratch_doubles.restype = ctypes.c_long
         _lib = L
     return _lib
 
@@ -134,3 +137,44 @@ def w4a16_gemm(x, packed, scales, zeros, group=128, out=None):
                                 _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
                                 _dev(y, torch.float16, "y"), _stream()), "sqp_w4a16_gemm")
     return y
+
+
+def quant_loss(x, w, x_hat, packed, scales, zeros, group=128, out=None):
+    """Eq. 4 for one layer: ||x w - x_hat w_hat||_F^2 as a one-element fp64 GPU tensor."""
+    M, K = x.shape
+    N = w.shape[1]
+    if w.shape[0] != K or tuple(x_hat.shape) != (M, K) or packed.shape[0] * 8 != K or packed.shape[1] != N:
+        raise SqpError("x, w, x_hat and packed disagree on the shape")
+    L = lib()
+    scratch = torch.empty(int(L.sqp_quant_loss_scratch_doubles(M, N)), dtype=torch.float64, device=x.device)
+    o = out if out is not None else torch.empty(1, dtype=torch.float64, device=x.device)
+    _check(L.sqp_quant_loss(M, N, K, group, _dev(x, torch.float16, "x"), _dev(w, torch.float16, "w"),
+                            _dev(x_hat, torch.float16, "x_hat"), _dev(packed, torch.int32, "packed"),
+                            _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
+                            _dev(scratch, torch.float64, "scratch"), _dev(o, torch.float64, "loss"), _stream()),
+           "sqp_quant_loss")
+    return o
+
+
+def alpha_search(x_cal, w, group=128, alphas=None):
+    """Single-layer search for the smoothing strength (Sec 2.2): for each alpha, Eq. 6 ->
+    Eq. 5 -> Eq. 1 -> Eq. 4 on the calibration activations, all in library kernels.
+    Returns (best alpha, list of (alpha, loss))."""
+    if alphas is None:
+        alphas = [0.05 * i for i in range(21)]
+    T, K = x_cal.shape
+    N = w.shape[1]
+    s = torch.empty(K, dtype=torch.float32, device=w.device)
+    xh = torch.empty_like(x_cal)
+    ws = torch.empty_like(w)
+    q = None
+    loss = torch.empty(len(alphas), dtype=torch.float64, device=w.device)
+    for i, a in enumerate(alphas):
+        smooth_scales(x_cal, w, float(a), out=s)
+        smooth_apply_x(x_cal, s, out=xh)
+        smooth_apply_w(w, s, out=ws)
+        q = quantize_pack(ws, group, out=q)
+        quant_loss(x_cal, w, xh, q[0], q[1], q[2], group, out=loss[i:i + 1])
+    vals = [float(v) for v in loss.cpu()]
+    best = min(range(len(alphas)), key=lambda i: vals[i])
+    return float(alphas[best]), list(zip([float(a) for a in alphas], vals))

@@ -1,0 +1,187 @@
+// Quantisation loss of one linear layer, Eq. 4 of arXiv 2312.03788:
+//   E = || X W - X_hat W_hat ||_F^2,   W_hat = dequantised 4-bit weights (Eq. 1),
+// with X_hat = X diag(s)^-1 and the quantised W_hat of diag(s) W (Eq. 5), as the search over the
+// smoothing strength alpha needs it (Sec 2.2: alpha is chosen to minimise the loss).
+//
+// The two products are never formed separately: rounding either of them to fp16 would
+// swamp their difference.  One fp32 accumulator per output element takes both, as a single
+// contraction over the concatenated inner dimension [X, X_hat] * [W; -W_hat]: per k-step one
+// MFMA with the fp16 weights and one with the negated dequantised codes.  A workgroup of 4
+// waves owns a 128 x 128 tile (wave tile 64 x 64 = 2 x 2 tiles of v_mfma_f32_32x32x16_f16),
+// squares and sums its accumulators in fp64 and writes one partial; a second kernel adds the
+// partials in a fixed order, so the result does not depend on scheduling.
+//   - X and X_hat tiles (128 rows x 32 k) go through LDS as they are (k is contiguous).
+//   - W is row-major [K][N], so a column's 8 consecutive k (one lane's B operand) are N apart:
+//     the tile is transposed on its way into LDS (8 rows x 2 columns per thread, v_perm_b32).
+//   - Packed words are loaded straight into registers (a word is one lane's B operand) and
+//     unpacked with the step negated.
+// This is an offline calibration kernel: plain loads and barriers, no hand pipelining.
+#include "sqp_common.h"
+#include "sqp_w4_unpack.h"
+
+namespace {
+
+constexpr int LBM = 128, LBN = 128, LBK = 32, LPAD = 8;  // row stride 80 bytes: 16-byte reads of 32 rows spread over the banks
+
+__global__ void __launch_bounds__(256)
+quant_loss_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, const h16 *__restrict__ w,
+                  const h16 *__restrict__ xh, const uint32_t *__restrict__ packed, const h16 *__restrict__ scales,
+                  const uint8_t *__restrict__ zeros, double *__restrict__ partials)
+{
+    __shared__ __attribute__((aligned(16))) h16 sx[LBM][LBK + LPAD];
+    __shared__ __attribute__((aligned(16))) h16 sxh[LBM][LBK + LPAD];
+    __shared__ __attribute__((aligned(16))) h16 sw[LBN][LBK + LPAD];  // transposed: [column][k]
+    __shared__ double red[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, kb = lane >> 5;
+    const int m0 = blockIdx.y * LBM, n0 = blockIdx.x * LBN;
+    const UnpackConsts uc = SQP_UNPACK_CONSTS;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+    // loader roles
+    const int arow = tid >> 1, apart = tid & 1;               // X, X_hat: row, 16-half part of the 32 k
+    int agrow = m0 + arow;
+    if (agrow >= M) agrow = M - 1;                             // rows past M: duplicates, masked at the end
+    const int wkb = tid >> 6, wcp = tid & 63;                  // W: k-block of 8 rows, column pair
+    const int wcol = n0 + 2 * wcp;
+
+    for (int k0 = 0; k0 < K; k0 += LBK) {
+        // ---- global -> LDS (K is a multiple of 8, so a group of 8 halves is in or out as a whole)
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const int kk = k0 + apart * 16 + j * 8;
+            uint4 vx = make_uint4(0, 0, 0, 0), vh = vx;
+            if (kk < K) {
+                vx = *reinterpret_cast<const uint4 *>(x + (size_t)agrow * K + kk);
+                vh = *reinterpret_cast<const uint4 *>(xh + (size_t)agrow * K + kk);
+            }
+            *reinterpret_cast<uint4 *>(&sx[arow][apart * 16 + j * 8]) = vx;
+            *reinterpret_cast<uint4 *>(&sxh[arow][apart * 16 + j * 8]) = vh;
+        }
+        {
+            uint32_t v[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const int kk = k0 + wkb * 8 + i;
+                v[i] = (kk < K && wcol < N) ? *reinterpret_cast<const uint32_t *>(w + (size_t)kk * N + wcol) : 0u;
+            }
+            uint4 c0, c1;  // column wcol: the low halves of the 8 rows; column wcol + 1: the high halves
+            c0.x = __builtin_amdgcn_perm(v[1], v[0], 0x05040100u); c1.x = __builtin_amdgcn_perm(v[1], v[0], 0x07060302u);
+            c0.y = __builtin_amdgcn_perm(v[3], v[2], 0x05040100u); c1.y = __builtin_amdgcn_perm(v[3], v[2], 0x07060302u);
+            c0.z = __builtin_amdgcn_perm(v[5], v[4], 0x05040100u); c1.z = __builtin_amdgcn_perm(v[5], v[4], 0x07060302u);
+            c0.w = __builtin_amdgcn_perm(v[7], v[6], 0x05040100u); c1.w = __builtin_amdgcn_perm(v[7], v[6], 0x07060302u);
+            *reinterpret_cast<uint4 *>(&sw[2 * wcp][wkb * 8]) = c0;
+            *reinterpret_cast<uint4 *>(&sw[2 * wcp + 1][wkb * 8]) = c1;
+        }
+        // ---- packed words of this wave's 64 columns: registers only
+        h16x8 bq[2][2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ks++)
+#pragma unroll
+            for (int t = 0; t < 2; t++) {
+                const int kk = k0 + ks * 16 + kb * 8;
+                const int col = n0 + wn * 64 + t * 32 + l32;
+                uint32_t word = 0, z = 0, d = 0;
+                if (kk < K && col < N) {
+                    const size_t gi = (size_t)(kk / group) * N + col;
+                    word = packed[(size_t)(kk >> 3) * N + col];
+                    z = zeros[gi];
+                    d = __builtin_bit_cast(uint16_t, scales[gi]) ^ 0x8000u;  // -Delta
+                }
+                bq[ks][t] = dequant_word_scaled(word, neg_hi_of(z), neg_lo_of(z), __builtin_bit_cast(h16x2, d * 0x00010001u), uc);
+            }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 2; ks++) {
+            h16x8 ax[2], ah[2], bw[2];
+#pragma unroll
+            for (int mt = 0; mt < 2; mt++) {
+                const int row = wm * 64 + mt * 32 + l32;
+                ax[mt] = *reinterpret_cast<const h16x8 *>(&sx[row][ks * 16 + kb * 8]);
+                ah[mt] = permute_x(*reinterpret_cast<const u32x4 *>(&sxh[row][ks * 16 + kb * 8]));
+            }
+#pragma unroll
+            for (int t = 0; t < 2; t++) bw[t] = *reinterpret_cast<const h16x8 *>(&sw[wn * 64 + t * 32 + l32][ks * 16 + kb * 8]);
+#pragma unroll
+            for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+                for (int t = 0; t < 2; t++) {
+                    acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ax[mt], bw[t], acc[mt][t], 0, 0, 0);
+                    acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[mt], bq[ks][t], acc[mt][t], 0, 0, 0);
+                }
+        }
+        __syncthreads();
+    }
+
+    // ---- sum of squares of the tile.  Accumulator register r of tile (mt, t): row
+    // 8*(r/4) + 4*(lane/32) + r%4 of the 32-row tile, column lane%32.
+    double ss = 0.0;
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            const int col = n0 + wn * 64 + t * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const int row = m0 + wm * 64 + mt * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
+                if (row < M && col < N) ss += (double)acc[mt][t][r] * (double)acc[mt][t][r];
+            }
+        }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if (lane == 0) red[wave] = ss;
+    __syncthreads();
+    if (tid == 0) partials[(size_t)blockIdx.y * gridDim.x + blockIdx.x] = ((red[0] + red[1]) + (red[2] + red[3]));
+}
+
+// Adds n partials in a fixed order: thread t takes t, t + 256, ..., then a tree over the block.
+__global__ void __launch_bounds__(256) sum_partials_kernel(const double *__restrict__ partials, long n, double *__restrict__ out)
+{
+    __shared__ double s[256];
+    double a = 0.0;
+    for (long i = threadIdx.x; i < n; i += 256) a += partials[i];
+    s[threadIdx.x] = a;
+    __syncthreads();
+    for (int half = 128; half >= 1; half >>= 1) {
+        if ((int)threadIdx.x < half) s[threadIdx.x] += s[threadIdx.x + half];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = s[0];
+}
+
+}  // namespace
+
+extern "C" long sqp_quant_loss_scratch_doubles(int M, int N)
+{
+    if (M <= 0 || N <= 0) return 0;
+    return (long)((M + LBM - 1) / LBM) * (long)((N + LBN - 1) / LBN);
+}
+
+extern "C" int sqp_quant_loss(int M, int N, int K, int group, const void *x, const void *w, const void *x_hat,
+                              const uint32_t *packed, const void *scales, const uint8_t *zeros, double *scratch,
+                              double *loss, void *stream)
+{
+    if (!x || !w || !x_hat || !packed || !scales || !zeros || !scratch || !loss) return SQP_ERR_NULL;
+    if (M <= 0) return SQP_ERR_SHAPE;
+    int rc = sqp_check_quant_shape(N, K, group);
+    if (rc) return rc;
+    if (sqp_misaligned(x) || sqp_misaligned(w) || sqp_misaligned(x_hat) || sqp_misaligned(packed) ||
+        sqp_misaligned(scales) || sqp_misaligned(zeros))
+        return SQP_ERR_ALIGN;
+    const int gy = (M + LBM - 1) / LBM, gx = (N + LBN - 1) / LBN;
+    if (gy > 65535) return SQP_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    quant_loss_kernel<<<dim3(gx, gy), 256, 0, st>>>(M, N, K, group, (const h16 *)x, (const h16 *)w, (const h16 *)x_hat,
+                                                   packed, (const h16 *)scales, zeros, scratch);
+    sum_partials_kernel<<<1, 256, 0, st>>>(scratch, (long)gx * gy, loss);
+    return sqp_launch_status();
+}
