@@ -84,9 +84,11 @@ int sqp_dequantize(int N, int K, int group, const uint32_t *packed, const void *
  * with fp32 accumulation and one rounding to fp16 at the end.  The result is
  * run-to-run deterministic.  x [M][K] fp16, y [M][N] fp16 out (must not alias x).
  * Rows M <= 64 take the weight-streaming (memory-bound) path, larger M the tiled
- * matrix-core path.  Some shapes use a library-owned device workspace that is
- * allocated on first use (so the first such call may allocate; concurrent calls on
- * different streams that both need it are serialised by the caller). */
+ * matrix-core path (with the inner dimension split across workgroups when the output has
+ * too few tiles to occupy the chip).  Some shapes use a library-owned device workspace
+ * (128 MB of fp32 partial sums per device) that is allocated on first use (so the first
+ * such call may allocate; concurrent calls on different streams that both need it are
+ * serialised by the caller). */
 int sqp_w4a16_gemm(int M, int N, int K, int group, const void *x, const uint32_t *packed,
                    const void *scales, const uint8_t *zeros, void *y, void *stream);
 

@@ -32,3 +32,5 @@ int sqp_gemm_decode(int M, int N, int K, int group, const h16 *x, const uint32_t
                     const h16 *scales, const uint8_t *zeros, h16 *y, hipStream_t stream);
 int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
                      const h16 *scales, const uint8_t *zeros, h16 *y, hipStream_t stream);
+// Library-owned device buffer for fp32 partial sums (allocated on first use).
+int sqp_partial_workspace(float **p, size_t *bytes, hipStream_t stream);

@@ -378,7 +378,7 @@ w4a16_generic_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
 
 // ---------------------------------------------------------------- workspace
 
-constexpr size_t WS_PARTIAL_BYTES = 64u << 20;
+constexpr size_t WS_PARTIAL_BYTES = (size_t)128 << 20;  // fp32 partial sums (decode split-K tiles, tiled-path K parts)
 constexpr int WS_TICKETS = 1 << 16;
 Workspace g_ws[16] = {};
 
@@ -407,6 +407,22 @@ int get_workspace(Workspace *out, hipStream_t st)
     return SQP_OK;
 }
 
+
+}  // namespace
+
+// The library's device workspace for fp32 partial sums, shared by both GEMM paths (calls on
+// one device are ordered by the caller's stream use, as the ABI header states).
+int sqp_partial_workspace(float **p, size_t *bytes, hipStream_t st)
+{
+    Workspace ws = {nullptr, nullptr};
+    int rc = get_workspace(&ws, st);
+    if (rc) return rc;
+    *p = ws.partial;
+    *bytes = WS_PARTIAL_BYTES;
+    return SQP_OK;
+}
+
+namespace {
 
 template <int MT, int NW, int KSPG>
 int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t *packed, const h16 *scales,

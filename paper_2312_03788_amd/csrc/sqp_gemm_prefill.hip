@@ -43,7 +43,7 @@ template <int NT, int W>
 __global__ void __launch_bounds__(W * 64)
 w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h16 *__restrict__ x,
                      const uint32_t *__restrict__ packed, const h16 *__restrict__ scales,
-                     const uint8_t *__restrict__ zeros, h16 *__restrict__ y)
+                     const uint8_t *__restrict__ zeros, h16 *__restrict__ y, float *__restrict__ part)
 {
     constexpr int WN = 32 * NT;            // columns per wave
     typedef uint32_t wvec __attribute__((ext_vector_type(NT)));
@@ -64,7 +64,11 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     const int nbase = (tile % tn) * 256 + (WGN == 256 ? 0 : ((int)blockIdx.x & 1) * 128);
     const int m0 = (tile / tn) * BM;
     const int n0 = nbase + wn * WN;
-    const int stages = K / BK;
+    // K split across gridDim.y workgroups (part != nullptr): this one takes stages
+    // [stage0, stage0 + stages) and leaves its fp32 sums in part[blockIdx.y][M][N].
+    const int stages_all = K / BK;
+    const int stage0 = (int)((long)stages_all * blockIdx.y / gridDim.y);
+    const int stages = (int)((long)stages_all * (blockIdx.y + 1) / gridDim.y) - stage0;
     const int spg = group / BK;            // stages per quantisation group
 
     int ncol = n0 + NT * l32;
@@ -88,12 +92,12 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     // The loading side walks the stages with wave-uniform byte pointers that are advanced by
     // constant strides (scalar adds only); past the last stage they stop, so that the padded
     // stages of the branch-free loop re-read the last one (cache hits).
-    const unsigned char *wq = reinterpret_cast<const unsigned char *>(packed);
-    const unsigned char *sq = reinterpret_cast<const unsigned char *>(scales);
-    const unsigned char *zq = zeros;
-    const unsigned char *xq = reinterpret_cast<const unsigned char *>(x);
     const long wrow2 = (long)N * 8;        // two packed rows (one k-step) in bytes
-    int ist = 0, kin = 0;                   // stage being issued, its position inside its group
+    const unsigned char *wq = reinterpret_cast<const unsigned char *>(packed) + (long)stage0 * 4 * wrow2;
+    const unsigned char *sq = reinterpret_cast<const unsigned char *>(scales) + (long)(stage0 / spg) * N * 2;
+    const unsigned char *zq = zeros + (long)(stage0 / spg) * N;
+    const unsigned char *xq = reinterpret_cast<const unsigned char *>(x) + (long)stage0 * (BK * 2);
+    int ist = 0, kin = stage0 % spg;        // stage being issued (relative), its position inside its group
     const uint32_t voff_w = (uint32_t)(kb * N + ncol) * 4u;
     const uint32_t voff_s = (uint32_t)ncol * 2u, voff_z = (uint32_t)ncol;
     auto issue_w = [&](Stage &s) {
@@ -347,6 +351,24 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     const int e_l32 = tid & 31, e_kb = (tid >> 5) & 1, e_wave = tid >> 6;
     const int nout = nbase + (e_wave % (W / 2)) * WN + NT * e_l32;
     const int mrow0 = m0 + (e_wave / (W / 2)) * 128 + 4 * e_kb;
+    if (part != nullptr) {
+        if (nout < N) {
+            float *pcol = part + (size_t)blockIdx.y * M * N + nout;
+#pragma unroll
+            for (int mt = 0; mt < 4; mt++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const int m = mrow0 + mt * 32 + 8 * (r >> 2) + (r & 3);
+                    if (m < M) {
+                        if constexpr (NT == 4)
+                            *reinterpret_cast<f32x4 *>(pcol + (size_t)m * N) = f32x4{acc[mt][0][r], acc[mt][1][r], acc[mt][2][r], acc[mt][3][r]};
+                        else
+                            *reinterpret_cast<float2 *>(pcol + (size_t)m * N) = make_float2(acc[mt][0][r], acc[mt][1][r]);
+                    }
+                }
+        }
+        return;
+    }
     if (nout < N) {
         h16 *ycol = y + nout;
 #pragma unroll
@@ -370,6 +392,26 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     }
 }
 
+// y = fp16(sum over the K parts, in part order) of the fp32 partial matrices: 8 elements
+// per thread.
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restrict__ part, long total8, long stride, int parts,
+                                                            h16 *__restrict__ y)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total8) return;
+    const f32x4 *p = reinterpret_cast<const f32x4 *>(part) + 2 * i;
+    f32x4 a = p[0], b = p[1];
+    for (int s = 1; s < parts; s++) {
+        const f32x4 *q = reinterpret_cast<const f32x4 *>(part + (size_t)s * stride) + 2 * i;
+        a += q[0];
+        b += q[1];
+    }
+    h16x8 o;
+    o.s0 = (h16)a.x; o.s1 = (h16)a.y; o.s2 = (h16)a.z; o.s3 = (h16)a.w;
+    o.s4 = (h16)b.x; o.s5 = (h16)b.y; o.s6 = (h16)b.z; o.s7 = (h16)b.w;
+    reinterpret_cast<h16x8 *>(y)[i] = o;
+}
+
 int compute_units()
 {
     static int cus = 0;  // same on every device of a node
@@ -389,36 +431,70 @@ int compute_units()
 #endif
 constexpr int MAIN_W = SQP_PF_MAIN_W, MAIN_NT = MAIN_W == 8 ? 2 : 4;
 
-// Test/benchmark hook: 0 = automatic tile choice, 1 = 256-column tiles only, 2 = 128-column
-// tiles only.
-static int g_tile_mode = 0;
+// Test/benchmark hooks.  Tiles: 0 = automatic tile choice, 1 = 256-column tiles only, 2 =
+// 128-column tiles only.  K split: -1 = automatic, 0 or 1 = never, k >= 2 = k parts.
+static int g_tile_mode = 0, g_ksplit = -1;
 extern "C" void sqp_debug_set_prefill_tiles(int mode) { g_tile_mode = mode; }
+extern "C" void sqp_debug_set_prefill_ksplit(int k) { g_ksplit = k; }
 
-int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
-                     const h16 *scales, const uint8_t *zeros, h16 *y, hipStream_t stream)
+// The weight-streaming kernel, 64 rows at a time.
+static int decode_in_row_blocks(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
+                                const h16 *scales, const uint8_t *zeros, h16 *y, hipStream_t stream)
 {
-    if (group % BK == 0) {
-        // One workgroup per compute unit is resident, so a launch proceeds in rounds of `cus`
-        // tiles.  When the last round would be at most half full, its tiles are done as twice
-        // as many half-width tiles by a second launch, which then costs about half a round.
-        const int tn = (N + 255) / 256, tm = (M + BM - 1) / BM;
-        const long tiles = (long)tn * tm;
-        const int cus = compute_units();
-        const long rounds = tiles / cus, left = tiles - rounds * cus;
-        long full = (left > 0 && 2 * left <= cus) ? rounds * cus : tiles;
-        if (g_tile_mode == 1) full = tiles;
-        if (g_tile_mode == 2) full = 0;
-        if (full > 0)
-            w4a16_prefill_kernel<MAIN_NT, MAIN_W><<<dim3((unsigned)full), MAIN_W * 64, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y);
-        if (full < tiles)
-            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)(2 * (tiles - full))), 256, 0, stream>>>(M, N, K, group, (int)full, tn, x, packed, scales, zeros, y);
-        return sqp_launch_status();
-    }
-    // group sizes the tiled kernel does not cover: the weight-streaming kernel, 64 rows at a time
     for (int mb = 0; mb < M; mb += 64) {
         int rows = M - mb < 64 ? M - mb : 64;
         int rc = sqp_gemm_decode(rows, N, K, group, x + (size_t)mb * K, packed, scales, zeros, y + (size_t)mb * N, stream);
         if (rc) return rc;
     }
     return SQP_OK;
+}
+
+int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
+                     const h16 *scales, const uint8_t *zeros, h16 *y, hipStream_t stream)
+{
+    if (group % BK == 0) {
+        const int tn = (N + 255) / 256, tm = (M + BM - 1) / BM;
+        const long tiles = (long)tn * tm;
+        const int cus = compute_units();
+        const int stages = K / BK;
+        // (1) Too few tiles to occupy the chip even as half-width tiles: split K as well.  Half
+        // tiles times K parts fill the compute units; every part leaves an fp32 [M][N] matrix in
+        // the library workspace and a second kernel adds the parts in order (deterministic).
+        int ksplit = 1;
+        if (g_tile_mode == 0 && 4 * tiles <= cus) {
+            ksplit = (int)(cus / (2 * tiles));
+            if (ksplit > stages / 8) ksplit = stages / 8;   // at least 8 stages per part
+            if (ksplit > 16) ksplit = 16;
+        }
+        if (g_ksplit >= 0) ksplit = g_ksplit;
+        if (ksplit > stages) ksplit = stages;
+        if (ksplit >= 2) {
+            float *part = nullptr;
+            size_t bytes = 0;
+            int rc = sqp_partial_workspace(&part, &bytes, stream);
+            if (rc) return rc;
+            const size_t per_part = (size_t)M * N * sizeof(float);
+            if ((size_t)ksplit * per_part > bytes) ksplit = (int)(bytes / per_part);
+            if (ksplit >= 2) {
+                w4a16_prefill_kernel<2, 4><<<dim3((unsigned)(2 * tiles), ksplit), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, part);
+                const long total8 = (long)M * N / 8;
+                splitk_reduce_kernel<<<(unsigned)((total8 + 255) / 256), 256, 0, stream>>>(part, total8, (long)M * N, ksplit, y);
+                return sqp_launch_status();
+            }
+        }
+        // (2) One workgroup per compute unit is resident, so a launch proceeds in rounds of `cus`
+        // tiles.  When the last round would be at most half full, its tiles are done as twice
+        // as many half-width tiles by a second launch, which then costs about half a round.
+        const long rounds = tiles / cus, left = tiles - rounds * cus;
+        long full = (left > 0 && 2 * left <= cus) ? rounds * cus : tiles;
+        if (g_tile_mode == 1) full = tiles;
+        if (g_tile_mode == 2) full = 0;
+        if (full > 0)
+            w4a16_prefill_kernel<MAIN_NT, MAIN_W><<<dim3((unsigned)full), MAIN_W * 64, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, nullptr);
+        if (full < tiles)
+            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)(2 * (tiles - full))), 256, 0, stream>>>(M, N, K, group, (int)full, tn, x, packed, scales, zeros, y, nullptr);
+        return sqp_launch_status();
+    }
+    // group sizes the tiled kernel does not cover
+    return decode_in_row_blocks(M, N, K, group, x, packed, scales, zeros, y, stream);
 }

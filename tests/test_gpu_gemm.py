@@ -157,6 +157,42 @@ def test_prefill_shapes(orc, sqp, M, K, N, group, tiles):
         L.sqp_debug_set_prefill_tiles(0)
 
 
+@pytest.mark.parametrize("M,K,N,group,ksplit", [
+    (300, 1024, 520, 128, 2), (300, 1024, 520, 128, 3), (65, 256, 264, 128, 2), (130, 384, 72, 64, 3),
+    (129, 512, 136, 256, 4), (257, 1024, 264, 128, 16)])
+def test_prefill_k_split(orc, sqp, M, K, N, group, ksplit):
+    """Tiled path with K split across workgroups (fp32 partial matrices added in part order):
+    parts that start inside a quantisation group, ragged M and N; twice, bit-identical."""
+    print("case prefill ksplit", M, K, N, group, ksplit, flush=True)
+    xs, p, sc, z = _layer(orc, M, K, N, group)
+    L = sqp.lib()
+    L.sqp_debug_set_prefill_ksplit(ksplit)
+    try:
+        y_ref, t_ref = orc.w4a16_gemm_ref(xs, p, sc, z, group)
+        args = (dev(xs), dev(p), dev(sc), dev(z), group)
+        y = host(sqp.w4a16_gemm(*args))
+        y2 = host(sqp.w4a16_gemm(*args))
+    finally:
+        L.sqp_debug_set_prefill_ksplit(-1)
+    assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
+    ok, worst, nbad = gemm_tolerance_ok(orc, y, y_ref, t_ref)
+    assert ok, "worst err/tol %.3f, %d elements out of tolerance" % (worst, nbad)
+
+
+def test_cfg4_34b_m256_sampled(orc, sqp):
+    """34B-shaped 8192 -> 8192 at M = 256 with the library's own plan (half-width tiles and a
+    K split): 24 sampled rows plus the first and last against the oracle."""
+    K, N, M = 8192, 8192, 256
+    print("case prefill 34b m256", M, K, N, flush=True)
+    xs, p, sc, z = _layer_cached(orc, M, K, N, 1)
+    rng = np.random.Generator(np.random.PCG64(13))
+    rows = np.unique(np.concatenate([[0, M - 1, 127, 128], rng.choice(M, 24, replace=False)]))
+    y_ref, t_ref = orc.w4a16_gemm_ref(np.ascontiguousarray(xs[rows]), p, sc, z, 128)
+    y = host(sqp.w4a16_gemm(dev(xs), dev(p), dev(sc), dev(z), 128))
+    ok, worst, nbad = gemm_tolerance_ok(orc, y[rows], y_ref, t_ref)
+    assert ok, "worst err/tol %.3f, %d elements out of tolerance" % (worst, nbad)
+
+
 def test_prefill_mixed_launch(orc, sqp):
     """A tile grid of one full round of 256 plus a remainder (N = 4352, M = 3968: 17 x 16 =
     272 tiles): the automatic choice runs 256 wide tiles and 32 narrow ones.  Sampled rows
