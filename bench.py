@@ -284,6 +284,30 @@ def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, 
     torch.cuda.synchronize()
     extra["alpha_search_21_ms"] = round((time.time() - t0) * 1e3, 1)
     extra["alpha_search_best"] = round(best, 2)
+    # context: the loss of plain round-to-nearest (no smoothing) on the same layer
+    qr = sqp.quantize_pack(w2, G)
+    e_rtn = float(sqp.quant_loss(xcal2, w2, xcal2, qr[0], qr[1], qr[2], G)[0])
+    e_best = min(v for _, v in curve)
+    extra["loss_rtn_over_best_alpha"] = round(e_rtn / e_best, 2)
+    del w2, xcal2, xh2, q2, qr
+    # context only (never a target): dense fp16 x fp16 GEMM of the vendor library through
+    # torch.matmul at the same shapes, weights rotating over >= 1.5 GB so that they stream from HBM
+    dense = {}
+    for (Kd, Nd) in shapes:
+        nl = max(2, int(1.5e9 / (2.0 * Kd * Nd)) + 1)
+        ws = [(torch.randn((Kd, Nd), device=dev, generator=gen, dtype=torch.float32) * 0.02).half() for _ in range(nl)]
+        for Md in (16, 2048):
+            xd = activation(Md, Kd, 2000 + Md)
+            yd = torch.empty((Md, Nd), device=dev, dtype=torch.float16)
+            state = {"i": 0}
+
+            def one():
+                torch.matmul(xd, ws[state["i"] % nl], out=yd)
+                state["i"] += 1
+            t = _time(torch, one, 2 * nl)
+            dense["%dx%d_m%d_us" % (Kd, Nd, Md)] = round(t * 1e6, 1)
+        del ws
+    extra["dense_fp16_vendor_gemm"] = dense
     return extra
 
 
