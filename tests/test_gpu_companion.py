@@ -85,7 +85,7 @@ def _weights(kind, K, N, seed):
 @pytest.mark.parametrize("kind,K,N,group", [
     ("smoothed", 1024, 1024, 128), ("normal", 256, 72, 128), ("edge", 512, 64, 128), ("edge", 256, 8, 32),
     ("normal", 384, 520, 64), ("normal", 512, 136, 256), ("normal", 48, 24, 24), ("edge", 64, 16, 8),
-    ("normal", 4096, 4096, 128), ("normal", 22016, 8192, 128)])
+    ("normal", 4096, 4096, 128), ("normal", 22016, 8192, 128), ("normal", 1024, 72, 1024), ("edge", 2048, 16, 2048)])
 def test_quantize_dequantize_bit_exact(orc, sqp, kind, K, N, group):
     print("case quantize", kind, K, N, group, flush=True)
     w = _weights(kind, K, N, seed=1234)

@@ -54,7 +54,8 @@ def test_decode_row_counts(orc, sqp, M):
 
 @pytest.mark.parametrize("M,K,N,group", [
     (3, 128, 8, 128), (5, 256, 72, 128), (16, 384, 520, 128), (9, 1152, 200, 128), (4, 256, 64, 32),
-    (16, 320, 136, 64), (33, 1024, 264, 256), (2, 48, 24, 24), (6, 64, 16, 8), (64, 2048, 1000, 128)])
+    (16, 320, 136, 64), (33, 1024, 264, 256), (2, 48, 24, 24), (6, 64, 16, 8), (64, 2048, 1000, 128),
+    (8, 1024, 264, 1024), (16, 2048, 136, 2048), (40, 1536, 72, 512)])  # the last three: one group per column / long groups
 def test_decode_ragged_shapes(orc, sqp, M, K, N, group):
     print("case ragged", M, K, N, group, flush=True)
     xs, p, sc, z = _layer(orc, M, K, N, group)
@@ -141,7 +142,8 @@ def _layer_cached(orc, M, K, N, shape_idx):
 
 @pytest.mark.parametrize("M,K,N,group", [
     (65, 256, 264, 128), (256, 512, 256, 64), (300, 1024, 520, 128), (130, 384, 72, 64),
-    (129, 512, 136, 256), (100, 128, 64, 32), (257, 192, 8, 64), (512, 2048, 1000, 128)])
+    (129, 512, 136, 256), (100, 128, 64, 32), (257, 192, 8, 64), (512, 2048, 1000, 128),
+    (130, 1024, 264, 1024)])
 @pytest.mark.parametrize("tiles", [0, 1, 2])
 def test_prefill_shapes(orc, sqp, M, K, N, group, tiles):
     """Tiled matrix-core path: full-output parity on shapes spanning several tiles with
@@ -159,7 +161,7 @@ def test_prefill_shapes(orc, sqp, M, K, N, group, tiles):
 
 @pytest.mark.parametrize("M,K,N,group,ksplit", [
     (300, 1024, 520, 128, 2), (300, 1024, 520, 128, 3), (65, 256, 264, 128, 2), (130, 384, 72, 64, 3),
-    (129, 512, 136, 256, 4), (257, 1024, 264, 128, 16)])
+    (129, 512, 136, 256, 4), (257, 1024, 264, 128, 16), (300, 1024, 520, 1024, 3)])
 def test_prefill_k_split(orc, sqp, M, K, N, group, ksplit):
     """Tiled path with K split across workgroups (fp32 partial matrices added in part order):
     parts that start inside a quantisation group, ragged M and N; twice, bit-identical."""
