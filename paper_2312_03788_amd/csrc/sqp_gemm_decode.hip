@@ -508,6 +508,18 @@ int sqp_gemm_generic(int M, int N, int K, int group, const h16 *x, const uint32_
     return sqp_launch_status();
 }
 
+// Test hook: the launch plan the library would pick for a shape (no launch, no GPU needed):
+// strips per workgroup, K split as requested by the heuristic, and the kernel family
+// (0 = generic, else k-steps per chunk).
+extern "C" void sqp_debug_decode_plan(int M, int N, int K, int group, int *nw, int *split, int *kspg)
+{
+    const int chunk = group % 128 == 0 ? 128 : group;
+    const Plan p = make_plan(M, N, K, chunk);
+    *nw = p.nw;
+    *split = p.split;
+    *kspg = group == 32 ? 1 : (group == 64 ? 2 : (group % 128 == 0 ? 4 : 0));
+}
+
 int sqp_gemm_decode(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
                     const uint8_t *zeros, h16 *y, hipStream_t stream)
 {

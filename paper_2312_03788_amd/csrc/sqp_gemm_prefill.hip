@@ -449,50 +449,82 @@ static int decode_in_row_blocks(int M, int N, int K, int group, const h16 *x, co
     return SQP_OK;
 }
 
+// Launch plan of the tiled path: `full` 256-column tiles in a first launch, then `half`
+// 128-column tiles (starting at tile `full`), the latter times `ksplit` K parts.
+struct TilePlan {
+    long full, half;
+    int ksplit;
+};
+
+static TilePlan plan_tiles(int M, int N, int K, int cus, size_t workspace_bytes)
+{
+    const int tn = (N + 255) / 256, tm = (M + BM - 1) / BM;
+    const long tiles = (long)tn * tm;
+    const int stages = K / BK;
+    TilePlan p = {tiles, 0, 1};
+    // (1) Too few tiles to occupy the chip even as half-width tiles: split K as well.  Half
+    // tiles times K parts fill the compute units; every part leaves an fp32 [M][N] matrix in
+    // the library workspace and a second kernel adds the parts in order (deterministic).
+    int ksplit = 1;
+    if (g_tile_mode == 0 && 4 * tiles <= cus) {
+        ksplit = (int)(cus / (2 * tiles));
+        if (ksplit > stages / 8) ksplit = stages / 8;   // at least 8 stages per part
+        if (ksplit > 16) ksplit = 16;
+    }
+    if (g_ksplit >= 0) ksplit = g_ksplit;
+    if (ksplit > stages) ksplit = stages;
+    const size_t per_part = (size_t)M * N * sizeof(float);
+    if ((size_t)ksplit * per_part > workspace_bytes) ksplit = (int)(workspace_bytes / per_part);
+    if (ksplit >= 2) {
+        p.full = 0;
+        p.half = 2 * tiles;
+        p.ksplit = ksplit;
+        return p;
+    }
+    // (2) One workgroup per compute unit is resident, so a launch proceeds in rounds of `cus`
+    // tiles.  When the last round would be at most half full, its tiles are done as twice
+    // as many half-width tiles by a second launch, which then costs about half a round.
+    const long rounds = tiles / cus, left = tiles - rounds * cus;
+    long full = (left > 0 && 2 * left <= cus) ? rounds * cus : tiles;
+    if (g_tile_mode == 1) full = tiles;
+    if (g_tile_mode == 2) full = 0;
+    p.full = full;
+    p.half = 2 * (tiles - full);
+    return p;
+}
+
+constexpr size_t PARTIAL_WORKSPACE_BYTES = (size_t)128 << 20;  // what sqp_partial_workspace provides
+
+// Test hook: the plan for a shape on a chip of `cus` compute units (no launch, no GPU needed).
+extern "C" void sqp_debug_prefill_plan(int M, int N, int K, int cus, long *full, long *half, int *ksplit)
+{
+    const TilePlan p = plan_tiles(M, N, K, cus, PARTIAL_WORKSPACE_BYTES);
+    *full = p.full;
+    *half = p.half;
+    *ksplit = p.ksplit;
+}
+
 int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
                      const h16 *scales, const uint8_t *zeros, h16 *y, hipStream_t stream)
 {
     if (group % BK == 0) {
-        const int tn = (N + 255) / 256, tm = (M + BM - 1) / BM;
-        const long tiles = (long)tn * tm;
-        const int cus = compute_units();
-        const int stages = K / BK;
-        // (1) Too few tiles to occupy the chip even as half-width tiles: split K as well.  Half
-        // tiles times K parts fill the compute units; every part leaves an fp32 [M][N] matrix in
-        // the library workspace and a second kernel adds the parts in order (deterministic).
-        int ksplit = 1;
-        if (g_tile_mode == 0 && 4 * tiles <= cus) {
-            ksplit = (int)(cus / (2 * tiles));
-            if (ksplit > stages / 8) ksplit = stages / 8;   // at least 8 stages per part
-            if (ksplit > 16) ksplit = 16;
-        }
-        if (g_ksplit >= 0) ksplit = g_ksplit;
-        if (ksplit > stages) ksplit = stages;
-        if (ksplit >= 2) {
+        const int tn = (N + 255) / 256;
+        TilePlan p = plan_tiles(M, N, K, compute_units(), PARTIAL_WORKSPACE_BYTES);
+        if (p.ksplit >= 2) {
             float *part = nullptr;
             size_t bytes = 0;
             int rc = sqp_partial_workspace(&part, &bytes, stream);
             if (rc) return rc;
-            const size_t per_part = (size_t)M * N * sizeof(float);
-            if ((size_t)ksplit * per_part > bytes) ksplit = (int)(bytes / per_part);
-            if (ksplit >= 2) {
-                w4a16_prefill_kernel<2, 4><<<dim3((unsigned)(2 * tiles), ksplit), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, part);
-                const long total8 = (long)M * N / 8;
-                splitk_reduce_kernel<<<(unsigned)((total8 + 255) / 256), 256, 0, stream>>>(part, total8, (long)M * N, ksplit, y);
-                return sqp_launch_status();
-            }
+            if ((size_t)p.ksplit * M * N * sizeof(float) > bytes) return SQP_ERR_WORKSPACE;
+            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)p.half, p.ksplit), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, part);
+            const long total8 = (long)M * N / 8;
+            splitk_reduce_kernel<<<(unsigned)((total8 + 255) / 256), 256, 0, stream>>>(part, total8, (long)M * N, p.ksplit, y);
+            return sqp_launch_status();
         }
-        // (2) One workgroup per compute unit is resident, so a launch proceeds in rounds of `cus`
-        // tiles.  When the last round would be at most half full, its tiles are done as twice
-        // as many half-width tiles by a second launch, which then costs about half a round.
-        const long rounds = tiles / cus, left = tiles - rounds * cus;
-        long full = (left > 0 && 2 * left <= cus) ? rounds * cus : tiles;
-        if (g_tile_mode == 1) full = tiles;
-        if (g_tile_mode == 2) full = 0;
-        if (full > 0)
-            w4a16_prefill_kernel<MAIN_NT, MAIN_W><<<dim3((unsigned)full), MAIN_W * 64, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, nullptr);
-        if (full < tiles)
-            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)(2 * (tiles - full))), 256, 0, stream>>>(M, N, K, group, (int)full, tn, x, packed, scales, zeros, y, nullptr);
+        if (p.full > 0)
+            w4a16_prefill_kernel<MAIN_NT, MAIN_W><<<dim3((unsigned)p.full), MAIN_W * 64, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, nullptr);
+        if (p.half > 0)
+            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)p.half), 256, 0, stream>>>(M, N, K, group, (int)p.full, tn, x, packed, scales, zeros, y, nullptr);
         return sqp_launch_status();
     }
     // group sizes the tiled kernel does not cover

@@ -1,0 +1,89 @@
+"""Host logic that needs no GPU: the launch plans the library derives from a shape (the
+decode path's strips and K split, the tiled path's tile mix and K parts) and the argument
+checks of the loss entry point."""
+import ctypes
+
+import pytest
+
+import workloads as wl
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2312_03788_amd as sqp
+    return sqp.lib()
+
+
+def _decode_plan(L, M, N, K, group):
+    nw, split, kspg = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    L.sqp_debug_decode_plan(M, N, K, group, ctypes.byref(nw), ctypes.byref(split), ctypes.byref(kspg))
+    return nw.value, split.value, kspg.value
+
+
+def _tile_plan(L, M, N, K, cus=256):
+    full, half, ks = ctypes.c_long(), ctypes.c_long(), ctypes.c_int()
+    L.sqp_debug_prefill_plan(M, N, K, cus, ctypes.byref(full), ctypes.byref(half), ctypes.byref(ks))
+    return full.value, half.value, ks.value
+
+
+def test_decode_plan_invariants(L):
+    shapes = [s for m in ("7b", "13b", "34b") for s in wl.MODEL_SHAPES[m]] + [(128, 8), (1024, 264), (65536, 64)]
+    for (K, N) in shapes:
+        for group in (32, 64, 128, 256):
+            if K % group:
+                continue
+            nw, split, kspg = _decode_plan(L, 16, N, K, group)
+            chunk = 128 if group % 128 == 0 else group
+            chunks = K // chunk
+            assert nw == 4 and kspg == {32: 1, 64: 2}.get(group, 4)
+            assert 1 <= split <= max(1, chunks // 4)          # at least four chunks per workgroup
+            tiles = -(-N // 256)
+            target = 256 if tiles <= 128 else 704
+            # as close to the target number of workgroups as the chunk bound allows
+            if split < max(1, chunks // 4):
+                assert abs(tiles * split - target) <= tiles
+    assert _decode_plan(L, 16, 1024, 1024, 24)[2] == 0        # other group sizes: generic kernel
+
+
+def test_decode_plan_34b_values(L):
+    """The plans the benchmark's launches run with (they are part of its configuration)."""
+    got = {(K, N): _decode_plan(L, 16, N, K, 128)[:2] for (K, N) in wl.MODEL_SHAPES["34b"]}
+    assert got == {(8192, 10240): (4, 6), (8192, 8192): (4, 8), (8192, 44032): (4, 4), (22016, 8192): (4, 8)}
+
+
+def test_tile_plan_invariants(L):
+    for M in (65, 128, 256, 300, 512, 1024, 2048, 4096):
+        for (K, N) in wl.MODEL_SHAPES["34b"] + [(1024, 264), (256, 8), (8192, 256)]:
+            for cus in (256, 304, 64):
+                full, half, ks = _tile_plan(L, M, N, K, cus)
+                tiles = -(-N // 256) * -(-M // 256)
+                assert full >= 0 and half >= 0 and ks >= 1
+                assert full + half // 2 == tiles and half % 2 == 0   # every tile exactly once
+                if ks >= 2:
+                    assert full == 0 and 4 * tiles <= cus
+                    assert half * ks <= cus                          # one round
+                    assert K // 64 // ks >= 8                        # at least 8 stages per part
+                    assert ks * M * N * 4 <= 128 << 20               # fits the workspace
+                else:
+                    assert full % cus == 0 or half == 0              # first launch: whole rounds only
+                    assert half <= cus                               # the remainder is one round
+
+
+def test_tile_plan_bench_shapes(L):
+    assert _tile_plan(L, 2048, 8192, 8192) == (256, 0, 1)
+    assert _tile_plan(L, 2048, 10240, 8192) == (256, 128, 1)
+    assert _tile_plan(L, 2048, 44032, 8192) == (1280, 192, 1)
+    assert _tile_plan(L, 256, 8192, 8192) == (0, 64, 4)
+
+
+def test_quant_loss_argument_errors(L):
+    P = ctypes.c_void_p
+    good, odd, null = P(0x1000), P(0x1008), P(0)
+    q = L.sqp_quant_loss
+    assert q(4, 1024, 1024, 128, good, good, good, good, good, good, null, good, null) == -1
+    assert q(0, 1024, 1024, 128, good, good, good, good, good, good, good, good, null) == -2
+    assert q(4, 1024, 1024, 100, good, good, good, good, good, good, good, good, null) == -2
+    assert q(4, 1024, 1024, 128, good, odd, good, good, good, good, good, good, null) == -3
+    assert L.sqp_quant_loss_scratch_doubles(512, 8192) == 4 * 64
+    assert L.sqp_quant_loss_scratch_doubles(129, 130) == 4
+    assert L.sqp_quant_loss_scratch_doubles(0, 8) == 0
