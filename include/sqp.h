@@ -65,6 +65,11 @@ int sqp_smooth_apply_x(int M, int K, const void *x, const float *s, void *x_out,
  * w, w_out [K][N] fp16 (may alias), s [K] fp32. */
 int sqp_smooth_apply_w(int K, int N, const void *w, const float *s, void *w_out, void *stream);
 
+/* Orientation helper: w_nk [N][K] fp16 (one row per output feature, as checkpoints store a
+ * linear layer) -> w_kn [K][N] fp16, the orientation of Eq. 2 (X W with W of shape Ci x Co) that
+ * every other entry point takes.  Exact copy of the values; the buffers must not overlap. */
+int sqp_transpose_nk(int N, int K, const void *w_nk, void *w_kn, void *stream);
+
 /* Group-wise asymmetric 4-bit quantisation of Eq. 1 along K (Sec 2.2) and packing.
  * For each column n and group t (rows t*group .. (t+1)*group-1):
  *   lo = min(min w, 0), hi = max(max w, 0)           (range widened to contain 0)

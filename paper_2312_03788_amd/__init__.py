@@ -5,7 +5,7 @@ Every operation runs in the HIP library; this package only marshals arguments
 if the library is missing or a call fails, an exception is raised.
 """
 from .binding import (SqpError, alpha_search, dequantize, lib, quantize_pack, quant_loss, smooth_apply_w,
-                      smooth_apply_x, smooth_scales, w4a16_gemm)
+                      smooth_apply_x, smooth_scales, transpose_nk, w4a16_gemm)
 
 __all__ = ["SqpError", "lib", "smooth_scales", "smooth_apply_x", "smooth_apply_w", "quantize_pack",
-           "dequantize", "w4a16_gemm", "quant_loss", "alpha_search"]
+           "dequantize", "w4a16_gemm", "quant_loss", "alpha_search", "transpose_nk"]

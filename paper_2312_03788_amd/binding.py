@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("SQP_LIBRARY", os.path.join(_HERE, "libsqp.so"))  # override: another build
 
 EXPORTS = ["sqp_status_string", "sqp_smooth_scales", "sqp_smooth_apply_x", "sqp_smooth_apply_w",
-           "sqp_quantize_pack", "sqp_dequantize", "sqp_w4a16_gemm", "sqp_quant_loss"]
+           "sqp_quantize_pack", "sqp_dequantize", "sqp_w4a16_gemm", "sqp_quant_loss", "sqp_transpose_nk"]
 
 
 class SqpError(RuntimeError):
@@ -40,6 +40,7 @@ def lib():
         L.sqp_dequantize.argtypes = [i, i, i, vp, vp, vp, vp, vp]
         L.sqp_w4a16_gemm.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp]
         L.sqp_quant_loss.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.sqp_transpose_nk.argtypes = [i, i, vp, vp, vp]
         L.sqp_quant_loss_scratch_doubles.argtypes = [i, i]
         for name in EXPORTS[1:]:
             getattr(L, name).restype = ctypes.c_int
@@ -137,6 +138,15 @@ def w4a16_gemm(x, packed, scales, zeros, group=128, out=None):
                                 _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
                                 _dev(y, torch.float16, "y"), _stream()), "sqp_w4a16_gemm")
     return y
+
+
+def transpose_nk(w_nk, out=None):
+    """[N,K] fp16 (checkpoint orientation) -> [K,N] fp16 (the orientation of Eq. 2)."""
+    N, K = w_nk.shape
+    o = out if out is not None else torch.empty((K, N), dtype=torch.float16, device=w_nk.device)
+    _check(lib().sqp_transpose_nk(N, K, _dev(w_nk, torch.float16, "w_nk"), _dev(o, torch.float16, "w_kn"), _stream()),
+           "sqp_transpose_nk")
+    return o
 
 
 def quant_loss(x, w, x_hat, packed, scales, zeros, group=128, out=None):

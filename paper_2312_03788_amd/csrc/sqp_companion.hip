@@ -312,6 +312,46 @@ extern "C" int sqp_smooth_apply_w(int K, int N, const void *w, const float *s, v
     return sqp_launch_status();
 }
 
+// fp16 [N][K] (one row per output feature, the orientation checkpoints store) -> [K][N] (the
+// orientation of Eq. 2 that every other entry point takes).  64 x 64 tile per workgroup through
+// LDS: 16-byte reads along K, 16-byte writes along N; the LDS row stride of 66 halves keeps the
+// 2-byte column reads of a wave on different banks.  grid: (K/64 rounded up, N/64 rounded up).
+__global__ void __launch_bounds__(256) transpose_nk_kernel(int N, int K, const h16 *__restrict__ in, h16 *__restrict__ out)
+{
+    __shared__ h16 tile[64][66];
+    const int k0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+    const int r = threadIdx.x >> 3, c8 = (threadIdx.x & 7) * 8;
+#pragma unroll
+    for (int rr = 0; rr < 64; rr += 32) {
+        const int n = n0 + r + rr, k = k0 + c8;
+        h16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (n < N && k < K) v = *reinterpret_cast<const h16x8 *>(in + (size_t)n * K + k);  // K % 8 == 0
+#pragma unroll
+        for (int i = 0; i < 8; i++) tile[r + rr][c8 + i] = v[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int rr = 0; rr < 64; rr += 32) {
+        const int k = k0 + r + rr, n = n0 + c8;
+        if (k < K && n < N) {                                                              // N % 8 == 0
+            h16x8 v;
+#pragma unroll
+            for (int i = 0; i < 8; i++) v[i] = tile[c8 + i][r + rr];
+            *reinterpret_cast<h16x8 *>(out + (size_t)k * N + n) = v;
+        }
+    }
+}
+
+extern "C" int sqp_transpose_nk(int N, int K, const void *w_nk, void *w_kn, void *stream)
+{
+    if (!w_nk || !w_kn) return SQP_ERR_NULL;
+    if (N <= 0 || K <= 0 || (N % 8) || (K % 8)) return SQP_ERR_SHAPE;
+    if (sqp_misaligned(w_nk) || sqp_misaligned(w_kn)) return SQP_ERR_ALIGN;
+    if ((N + 63) / 64 > 65535) return SQP_ERR_SHAPE;
+    transpose_nk_kernel<<<dim3((K + 63) / 64, (N + 63) / 64), 256, 0, (hipStream_t)stream>>>(N, K, (const h16 *)w_nk, (h16 *)w_kn);
+    return sqp_launch_status();
+}
+
 extern "C" int sqp_quantize_pack(int N, int K, int group, const void *w, uint32_t *packed, void *scales, uint8_t *zeros, void *stream)
 {
     if (!w || !packed || !scales || !zeros) return SQP_ERR_NULL;

@@ -107,3 +107,12 @@ def test_dequantize_random_words(orc, sqp):
     z = rng.integers(0, 16, size=(K // g, N)).astype(np.uint8)
     what = host(sqp.dequantize(dev(p), dev(s), dev(z), g))
     assert np.array_equal(what.view(np.uint16), orc.dequantize(p, s, z, g).view(np.uint16))
+
+
+@pytest.mark.parametrize("N,K", [(8, 8), (72, 264), (1000, 520), (4096, 11008), (64, 64)])
+def test_transpose_nk(sqp, N, K):
+    """[N][K] -> [K][N]: an exact copy of every value (compared with numpy's transpose)."""
+    rng = np.random.Generator(np.random.PCG64(N * 7 + K))
+    w = rng.integers(0, 65536, size=(N, K), dtype=np.uint16)  # every bit pattern, NaNs included
+    got = host(sqp.transpose_nk(dev(w.view(np.float16)))).view(np.uint16)
+    assert np.array_equal(got, np.ascontiguousarray(w.T))
