@@ -201,3 +201,53 @@ def ulp16(v):
     e = np.floor(np.log2(np.maximum(a, 2.0 ** -14)))
     e = np.clip(e, -14, 15)
     return 2.0 ** (e - 10)
+
+
+# ---------------------------------------------------------------------------------------------
+# LlamaMLP block with the smoothing factors folded into the preceding layers (Sec 2.2, Fig. 5):
+# plain fp64 definitions in numpy.  Test infrastructure like the rest of this package.
+
+def rmsnorm_ref(x, gamma, eps):
+    """LlamaRMSNorm in fp64: x / sqrt(mean(x^2) + eps) * gamma, rows of x [M,H]; returns float64."""
+    x = np.asarray(x, np.float64)
+    g = np.asarray(gamma, np.float64)
+    r = np.sqrt(np.mean(x * x, axis=1, keepdims=True) + float(eps))
+    return x / r * g
+
+
+def silu_ref(g):
+    """SiLU(g) = g * sigmoid(g) = g / (1 + exp(-g)) in fp64."""
+    g = np.asarray(g, np.float64)
+    return g / (1.0 + np.exp(-g))
+
+
+def silu_mul_ref(gate, up):
+    """The LlamaMLP activation: SiLU(gate) * up, fp64."""
+    return silu_ref(gate) * np.asarray(up, np.float64)
+
+
+def scale_columns(w, s):
+    """w[k][n] / s[n]: fp32 divide, one rounding to fp16 (the division of down_proj's input by its
+    smoothing factor, folded into up_proj's output columns)."""
+    w = _c(w, np.float16)
+    s = _c(s, np.float32)
+    return (w.astype(np.float32) / s[None, :]).astype(np.float16)
+
+
+def interleave_gate_up(w_gate, w_up):
+    """[K,I] x 2 -> [K,2I] with column 2j = gate j, column 2j+1 = up j (the merged layout whose
+    GEMM epilogue can form SiLU(gate) * up from adjacent columns)."""
+    w_gate = _c(w_gate, np.float16)
+    w_up = _c(w_up, np.float16)
+    K, I = w_gate.shape
+    out = np.empty((K, 2 * I), np.float16)
+    out[:, 0::2] = w_gate
+    out[:, 1::2] = w_up
+    return out
+
+
+def mlp_block_ref(x, gamma, eps, w_gate, w_up, w_down):
+    """The unquantised, unsmoothed block in fp64: down(SiLU(gate(n)) * up(n)), n = RMSNorm(x)."""
+    n = rmsnorm_ref(x, gamma, eps)
+    h = silu_mul_ref(n @ np.asarray(w_gate, np.float64), n @ np.asarray(w_up, np.float64))
+    return h @ np.asarray(w_down, np.float64)
