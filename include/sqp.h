@@ -65,6 +65,30 @@ int sqp_smooth_apply_x(int M, int K, const void *x, const float *s, void *x_out,
  * w, w_out [K][N] fp16 (may alias), s [K] fp32. */
 int sqp_smooth_apply_w(int K, int N, const void *w, const float *s, void *w_out, void *stream);
 
+/* The merged gate/up projection of a LlamaMLP block with its activation fused (Fig. 5: the
+ * block whose smoothing factors are folded into the preceding layers).  packed/scales/zeros
+ * hold the quantised merged weight [K][N] whose columns alternate (gate j, up j)
+ * (sqp_interleave_gate_up); the result is
+ *   y[m][j] = fp16( SiLU(g) * u ),  g, u = the fp32 sums of Eq. 3 for columns 2j and 2j+1,
+ * y [M][N/2] fp16.  N % 16 == 0; group 32, 64 or a multiple of 128.  Otherwise as sqp_w4a16_gemm. */
+int sqp_w4a16_gemm_silu_mul(int M, int N, int K, int group, const void *x, const uint32_t *packed,
+                            const void *scales, const uint8_t *zeros, void *y, void *stream);
+
+/* LlamaRMSNorm: y[m][j] = fp16( x[m][j] / sqrt(mean_j x[m][j]^2 + eps) * gamma[j] ), fp32
+ * arithmetic.  gamma [H] fp16 may already contain the division by the smoothing factor of the
+ * layers it feeds (Sec 2.2: fused into post_attention_layernorm; fold it with
+ * sqp_smooth_apply_x on the 1 x H weight).  x, y [M][H] fp16, H % 8 == 0, 0 <= eps < 1. */
+int sqp_rmsnorm(int M, int H, const void *x, const void *gamma, float eps, void *y, void *stream);
+
+/* w_out[k][n] = fp16(w[k][n] / s[n]): divides the OUTPUT columns of a layer by the smoothing
+ * factor of the layer it feeds (Sec 2.2: down_proj's factor fused into up_proj's weights).
+ * w, w_out [K][N] fp16 (may alias), s [N] fp32, N % 8 == 0. */
+int sqp_scale_columns(int K, int N, const void *w, const float *s, void *w_out, void *stream);
+
+/* w_out [K][2I] with column 2j = w_gate[.][j] and column 2j+1 = w_up[.][j] (exact copies), the
+ * merged layout sqp_w4a16_gemm_silu_mul expects.  w_gate, w_up [K][I] fp16, I % 8 == 0. */
+int sqp_interleave_gate_up(int K, int I, const void *w_gate, const void *w_up, void *w_out, void *stream);
+
 /* Orientation helper: w_nk [N][K] fp16 (one row per output feature, as checkpoints store a
  * linear layer) -> w_kn [K][N] fp16, the orientation of Eq. 2 (X W with W of shape Ci x Co) that
  * every other entry point takes.  Exact copy of the values; the buffers must not overlap. */

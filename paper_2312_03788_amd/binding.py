@@ -13,7 +13,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("SQP_LIBRARY", os.path.join(_HERE, "libsqp.so"))  # override: another build
 
 EXPORTS = ["sqp_status_string", "sqp_smooth_scales", "sqp_smooth_apply_x", "sqp_smooth_apply_w",
-           "sqp_quantize_pack", "sqp_dequantize", "sqp_w4a16_gemm", "sqp_quant_loss", "sqp_transpose_nk"]
+           "sqp_quantize_pack", "sqp_dequantize", "sqp_w4a16_gemm", "sqp_quant_loss", "sqp_transpose_nk",
+           "sqp_w4a16_gemm_silu_mul", "sqp_rmsnorm", "sqp_scale_columns", "sqp_interleave_gate_up"]
 
 
 class SqpError(RuntimeError):
@@ -41,6 +42,10 @@ def lib():
         L.sqp_w4a16_gemm.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp]
         L.sqp_quant_loss.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.sqp_transpose_nk.argtypes = [i, i, vp, vp, vp]
+        L.sqp_w4a16_gemm_silu_mul.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp]
+        L.sqp_rmsnorm.argtypes = [i, i, vp, vp, f, vp, vp]
+        L.sqp_scale_columns.argtypes = [i, i, vp, vp, vp, vp]
+        L.sqp_interleave_gate_up.argtypes = [i, i, vp, vp, vp, vp]
         L.sqp_quant_loss_scratch_doubles.argtypes = [i, i]
         for name in EXPORTS[1:]:
             getattr(L, name).restype = ctypes.c_int
@@ -138,6 +143,46 @@ def w4a16_gemm(x, packed, scales, zeros, group=128, out=None):
                                 _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
                                 _dev(y, torch.float16, "y"), _stream()), "sqp_w4a16_gemm")
     return y
+
+
+def w4a16_gemm_silu_mul(x, packed, scales, zeros, group=128, out=None):
+    """Merged, interleaved gate/up projection with SiLU(gate) * up fused: y [M, N/2] fp16."""
+    M, K = x.shape
+    N = packed.shape[1]
+    if packed.shape[0] * 8 != K:
+        raise SqpError("x and packed disagree on K")
+    y = out if out is not None else torch.empty((M, N // 2), dtype=torch.float16, device=x.device)
+    _check(lib().sqp_w4a16_gemm_silu_mul(M, N, K, group, _dev(x, torch.float16, "x"), _dev(packed, torch.int32, "packed"),
+                                         _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
+                                         _dev(y, torch.float16, "y"), _stream()), "sqp_w4a16_gemm_silu_mul")
+    return y
+
+
+def rmsnorm(x, gamma, eps, out=None):
+    """LlamaRMSNorm with an fp16 weight (possibly already divided by a smoothing factor)."""
+    M, H = x.shape
+    y = out if out is not None else torch.empty_like(x)
+    _check(lib().sqp_rmsnorm(M, H, _dev(x, torch.float16, "x"), _dev(gamma, torch.float16, "gamma"), float(eps),
+                             _dev(y, torch.float16, "y"), _stream()), "sqp_rmsnorm")
+    return y
+
+
+def scale_columns(w, s, out=None):
+    """w[k][n] / s[n] in fp16: a smoothing factor folded into the producing layer's columns."""
+    K, N = w.shape
+    o = out if out is not None else torch.empty_like(w)
+    _check(lib().sqp_scale_columns(K, N, _dev(w, torch.float16, "w"), _dev(s, torch.float32, "s"),
+                                   _dev(o, torch.float16, "w_out"), _stream()), "sqp_scale_columns")
+    return o
+
+
+def interleave_gate_up(w_gate, w_up, out=None):
+    """[K,I] x 2 -> [K,2I], column 2j = gate j, column 2j+1 = up j."""
+    K, I = w_gate.shape
+    o = out if out is not None else torch.empty((K, 2 * I), dtype=torch.float16, device=w_gate.device)
+    _check(lib().sqp_interleave_gate_up(K, I, _dev(w_gate, torch.float16, "w_gate"), _dev(w_up, torch.float16, "w_up"),
+                                        _dev(o, torch.float16, "w_out"), _stream()), "sqp_interleave_gate_up")
+    return o
 
 
 def transpose_nk(w_nk, out=None):

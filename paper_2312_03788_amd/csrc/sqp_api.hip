@@ -79,8 +79,8 @@ static int g_decode_max_m = 64;
 // Test/benchmark hook: rows up to which the weight-streaming path is used.
 extern "C" void sqp_debug_set_decode_max_m(int m) { g_decode_max_m = m; }
 
-extern "C" int sqp_w4a16_gemm(int M, int N, int K, int group, const void *x, const uint32_t *packed,
-                              const void *scales, const uint8_t *zeros, void *y, void *stream)
+static int gemm_entry(int M, int N, int K, int group, const void *x, const uint32_t *packed, const void *scales,
+                      const uint8_t *zeros, void *y, int epi, void *stream)
 {
     if (!x || !packed || !scales || !zeros || !y) return SQP_ERR_NULL;
     if (M <= 0) return SQP_ERR_SHAPE;
@@ -92,6 +92,21 @@ extern "C" int sqp_w4a16_gemm(int M, int N, int K, int group, const void *x, con
     const h16 *xp = (const h16 *)x;
     const h16 *sp = (const h16 *)scales;
     h16 *yp = (h16 *)y;
-    if (M <= g_decode_max_m && M <= 64) return sqp_gemm_decode(M, N, K, group, xp, packed, sp, zeros, yp, st);
-    return sqp_gemm_prefill(M, N, K, group, xp, packed, sp, zeros, yp, st);
+    if (M <= g_decode_max_m && M <= 64) return sqp_gemm_decode(M, N, K, group, xp, packed, sp, zeros, yp, epi, st);
+    return sqp_gemm_prefill(M, N, K, group, xp, packed, sp, zeros, yp, epi, st);
+}
+
+extern "C" int sqp_w4a16_gemm(int M, int N, int K, int group, const void *x, const uint32_t *packed,
+                              const void *scales, const uint8_t *zeros, void *y, void *stream)
+{
+    return gemm_entry(M, N, K, group, x, packed, scales, zeros, y, 0, stream);
+}
+
+extern "C" int sqp_w4a16_gemm_silu_mul(int M, int N, int K, int group, const void *x, const uint32_t *packed,
+                                       const void *scales, const uint8_t *zeros, void *y, void *stream)
+{
+    if (N % 16) return SQP_ERR_SHAPE;          // the half-width output keeps 16-byte rows
+    // the fused epilogue exists in the matrix-core kernels only
+    if (!(group == 32 || group == 64 || group % 128 == 0)) return SQP_ERR_SHAPE;
+    return gemm_entry(M, N, K, group, x, packed, scales, zeros, y, 1, stream);
 }

@@ -28,9 +28,15 @@ static inline int sqp_launch_status()
 
 // Decode (weight-streaming) and prefill (tiled matrix-core) back ends of sqp_w4a16_gemm.
 // Arguments are already validated.
+// epi: 0 = y [M][N] fp16; 1 = SiLU(gate) * up of interleaved (gate, up) column pairs, y [M][N/2].
 int sqp_gemm_decode(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
-                    const h16 *scales, const uint8_t *zeros, h16 *y, hipStream_t stream);
+                    const h16 *scales, const uint8_t *zeros, h16 *y, int epi, hipStream_t stream);
 int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
-                     const h16 *scales, const uint8_t *zeros, h16 *y, hipStream_t stream);
+                     const h16 *scales, const uint8_t *zeros, h16 *y, int epi, hipStream_t stream);
+
+#ifdef __HIPCC__
+// SiLU(g) = g / (1 + exp(-g)) in fp32 (the hardware exponential: about 1 ulp of fp32).
+__device__ __forceinline__ float sqp_silu(float g) { return g / (1.0f + __expf(-g)); }
+#endif
 // Library-owned device buffer for fp32 partial sums (allocated on first use).
 int sqp_partial_workspace(float **p, size_t *bytes, hipStream_t stream);

@@ -41,6 +41,24 @@ struct Workspace {
     unsigned *tickets;   // [tiles], zero between launches
 };
 
+// Final store of 4 adjacent columns n .. n+3 of row m.  epi == 0: the fp16 values themselves,
+// y [M][N].  epi == 1: the columns are (gate j, up j, gate j+1, up j+1) of a merged,
+// interleaved gate/up projection and the output is SiLU(gate) * up, y [M][N/2] (the LlamaMLP
+// activation of Fig. 5, formed from the fp32 sums before any rounding).
+__device__ __forceinline__ void store_row4(h16 *y, int m, int N, int n, int epi, float a0, float a1, float a2, float a3)
+{
+    if (epi == 0) {
+        h16x4 o;
+        o.x = (h16)a0; o.y = (h16)a1; o.z = (h16)a2; o.w = (h16)a3;
+        *reinterpret_cast<h16x4 *>(y + (size_t)m * N + n) = o;
+    } else {
+        h16x2 o;
+        o.x = (h16)(sqp_silu(a0) * a1);
+        o.y = (h16)(sqp_silu(a2) * a3);
+        *reinterpret_cast<h16x2 *>(y + (size_t)m * (N >> 1) + (n >> 1)) = o;
+    }
+}
+
 // MT: 16-row tiles of x (M <= 16*MT).  NW: waves (64-column strips) per workgroup.
 // KSPG: k-steps (of 32) per chunk; a quantisation group is cpg chunks (cpg = 1 unless the
 // group is a multiple of 128 above 128).
@@ -48,7 +66,7 @@ template <int MT, int NW, int KSPG>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MT == 1 && NW >= 4 ? 3 : 1)))
 w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, const uint32_t *__restrict__ packed,
                     const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y,
-                    Workspace ws)
+                    Workspace ws, int epi)
 {
     constexpr int D = SQP_DECODE_DEPTH;    // register stages of packed weights
     constexpr int XD = D;                  // LDS slots of activations
@@ -271,12 +289,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 #pragma unroll
                 for (int r = 0; r < 4; r++) {
                     const int m = mt * 16 + 4 * lk + r;
-                    if (m < M) {
-                        h16x4 o;
-                        o.x = (h16)acc[mt][0][r]; o.y = (h16)acc[mt][1][r];
-                        o.z = (h16)acc[mt][2][r]; o.w = (h16)acc[mt][3][r];
-                        *reinterpret_cast<h16x4 *>(y + (size_t)m * N + nout) = o;
-                    }
+                    if (m < M) store_row4(y, m, N, nout, epi, acc[mt][0][r], acc[mt][1][r], acc[mt][2][r], acc[mt][3][r]);
                 }
         }
         return;
@@ -336,12 +349,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 #pragma unroll
                 for (int r = 0; r < 4; r++) {
                     const int m = mt * 16 + 4 * lk + r;
-                    if (m < M) {
-                        h16x4 o;
-                        o.x = (h16)sum[mt * 4 + 0][r]; o.y = (h16)sum[mt * 4 + 1][r];
-                        o.z = (h16)sum[mt * 4 + 2][r]; o.w = (h16)sum[mt * 4 + 3][r];
-                        *reinterpret_cast<h16x4 *>(y + (size_t)m * N + nout) = o;
-                    }
+                    if (m < M) store_row4(y, m, N, nout, epi, sum[mt * 4 + 0][r], sum[mt * 4 + 1][r], sum[mt * 4 + 2][r], sum[mt * 4 + 3][r]);
                 }
         }
     }
@@ -426,7 +434,7 @@ namespace {
 
 template <int MT, int NW, int KSPG>
 int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t *packed, const h16 *scales,
-           const uint8_t *zeros, h16 *y, hipStream_t st)
+           const uint8_t *zeros, h16 *y, int epi, hipStream_t st)
 {
     constexpr int BN = 64 * NW;
     const int tiles = (N + BN - 1) / BN;
@@ -442,7 +450,7 @@ int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t
         int rc = get_workspace(&ws, st);
         if (rc) return rc;
     }
-    w4a16_decode_kernel<MT, NW, KSPG><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws);
+    w4a16_decode_kernel<MT, NW, KSPG><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
     return sqp_launch_status();
 }
 
@@ -474,22 +482,22 @@ Plan make_plan(int M, int N, int K, int chunk)
 
 template <int MT, int KSPG>
 int dispatch_mt(const Plan &p, int M, int N, int K, int cpg, const h16 *x, const uint32_t *packed, const h16 *scales,
-                const uint8_t *zeros, h16 *y, hipStream_t st)
+                const uint8_t *zeros, h16 *y, int epi, hipStream_t st)
 {
-    if (p.nw == 1) return launch<MT, 1, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
-    if (p.nw == 2) return launch<MT, 2, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
+    if (p.nw == 1) return launch<MT, 1, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, st);
+    if (p.nw == 2) return launch<MT, 2, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, st);
     if constexpr (MT < 4)  // eight waves of the 64-row variant would not fit the register file
-        if (p.nw == 8) return launch<MT, 8, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
-    return launch<MT, 4, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, st);
+        if (p.nw == 8) return launch<MT, 8, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, st);
+    return launch<MT, 4, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, st);
 }
 
 template <int KSPG>
 int dispatch_kspg(const Plan &p, int M, int N, int K, int cpg, const h16 *x, const uint32_t *packed, const h16 *scales,
-                  const uint8_t *zeros, h16 *y, hipStream_t st)
+                  const uint8_t *zeros, h16 *y, int epi, hipStream_t st)
 {
-    if (M <= 16) return dispatch_mt<1, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, st);
-    if (M <= 32) return dispatch_mt<2, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, st);
-    return dispatch_mt<4, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, st);
+    if (M <= 16) return dispatch_mt<1, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, epi, st);
+    if (M <= 32) return dispatch_mt<2, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, epi, st);
+    return dispatch_mt<4, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, epi, st);
 }
 
 }  // namespace
@@ -521,14 +529,15 @@ extern "C" void sqp_debug_decode_plan(int M, int N, int K, int group, int *nw, i
 }
 
 int sqp_gemm_decode(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
-                    const uint8_t *zeros, h16 *y, hipStream_t stream)
+                    const uint8_t *zeros, h16 *y, int epi, hipStream_t stream)
 {
     const int chunk = group % 128 == 0 ? 128 : group;
     Plan p = make_plan(M, N, K, chunk);
     if (g_force_plan.nw > 0) p = g_force_plan;
     if (g_force_split > 0) p.split = g_force_split;
-    if (group == 32) return dispatch_kspg<1>(p, M, N, K, 1, x, packed, scales, zeros, y, stream);
-    if (group == 64) return dispatch_kspg<2>(p, M, N, K, 1, x, packed, scales, zeros, y, stream);
-    if (group % 128 == 0) return dispatch_kspg<4>(p, M, N, K, group / 128, x, packed, scales, zeros, y, stream);
+    if (group == 32) return dispatch_kspg<1>(p, M, N, K, 1, x, packed, scales, zeros, y, epi, stream);
+    if (group == 64) return dispatch_kspg<2>(p, M, N, K, 1, x, packed, scales, zeros, y, epi, stream);
+    if (group % 128 == 0) return dispatch_kspg<4>(p, M, N, K, group / 128, x, packed, scales, zeros, y, epi, stream);
+    if (epi != 0) return SQP_ERR_SHAPE;  // the fused activation needs a group size the matrix-core kernels cover
     return sqp_gemm_generic(M, N, K, group, x, packed, scales, zeros, y, stream);
 }

@@ -43,7 +43,7 @@ template <int NT, int W>
 __global__ void __launch_bounds__(W * 64)
 w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h16 *__restrict__ x,
                      const uint32_t *__restrict__ packed, const h16 *__restrict__ scales,
-                     const uint8_t *__restrict__ zeros, h16 *__restrict__ y, float *__restrict__ part)
+                     const uint8_t *__restrict__ zeros, h16 *__restrict__ y, float *__restrict__ part, int epi)
 {
     constexpr int WN = 32 * NT;            // columns per wave
     typedef uint32_t wvec __attribute__((ext_vector_type(NT)));
@@ -377,7 +377,18 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
             for (int r = 0; r < 16; r++) {
                 const int m = mrow0 + mt * 32 + 8 * (r >> 2) + (r & 3);
                 if (m < M) {
-                    if constexpr (NT == 4) {
+                    if (epi != 0) {
+                        // adjacent columns are (gate j, up j): y [M][N/2] = SiLU(gate) * up
+                        h16 *yh = y + (size_t)m * (N >> 1) + (nout >> 1);
+                        if constexpr (NT == 4) {
+                            h16x2 o;
+                            o.x = (h16)(sqp_silu(acc[mt][0][r]) * acc[mt][1][r]);
+                            o.y = (h16)(sqp_silu(acc[mt][2][r]) * acc[mt][3][r]);
+                            *reinterpret_cast<h16x2 *>(yh) = o;
+                        } else {
+                            *yh = (h16)(sqp_silu(acc[mt][0][r]) * acc[mt][1][r]);
+                        }
+                    } else if constexpr (NT == 4) {
                         h16x4 o;
                         o.x = (h16)acc[mt][0][r]; o.y = (h16)acc[mt][1][r];
                         o.z = (h16)acc[mt][2][r]; o.w = (h16)acc[mt][3][r];
@@ -395,7 +406,7 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
 // y = fp16(sum over the K parts, in part order) of the fp32 partial matrices: 8 elements
 // per thread.
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restrict__ part, long total8, long stride, int parts,
-                                                            h16 *__restrict__ y)
+                                                            h16 *__restrict__ y, int epi)
 {
     const long i = (long)blockIdx.x * 256 + threadIdx.x;
     if (i >= total8) return;
@@ -405,6 +416,13 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restr
         const f32x4 *q = reinterpret_cast<const f32x4 *>(part + (size_t)s * stride) + 2 * i;
         a += q[0];
         b += q[1];
+    }
+    if (epi != 0) {  // (gate, up) pairs -> SiLU(gate) * up; 8 adjacent columns of [M][N] are 4 of [M][N/2]
+        h16x4 o;
+        o.x = (h16)(sqp_silu(a.x) * a.y); o.y = (h16)(sqp_silu(a.z) * a.w);
+        o.z = (h16)(sqp_silu(b.x) * b.y); o.w = (h16)(sqp_silu(b.z) * b.w);
+        reinterpret_cast<h16x4 *>(y)[i] = o;
+        return;
     }
     h16x8 o;
     o.s0 = (h16)a.x; o.s1 = (h16)a.y; o.s2 = (h16)a.z; o.s3 = (h16)a.w;
@@ -439,11 +457,12 @@ extern "C" void sqp_debug_set_prefill_ksplit(int k) { g_ksplit = k; }
 
 // The weight-streaming kernel, 64 rows at a time.
 static int decode_in_row_blocks(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
-                                const h16 *scales, const uint8_t *zeros, h16 *y, hipStream_t stream)
+                                const h16 *scales, const uint8_t *zeros, h16 *y, int epi, hipStream_t stream)
 {
+    const size_t ystride = epi != 0 ? (size_t)(N >> 1) : (size_t)N;
     for (int mb = 0; mb < M; mb += 64) {
         int rows = M - mb < 64 ? M - mb : 64;
-        int rc = sqp_gemm_decode(rows, N, K, group, x + (size_t)mb * K, packed, scales, zeros, y + (size_t)mb * N, stream);
+        int rc = sqp_gemm_decode(rows, N, K, group, x + (size_t)mb * K, packed, scales, zeros, y + (size_t)mb * ystride, epi, stream);
         if (rc) return rc;
     }
     return SQP_OK;
@@ -505,7 +524,7 @@ extern "C" void sqp_debug_prefill_plan(int M, int N, int K, int cus, long *full,
 }
 
 int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
-                     const h16 *scales, const uint8_t *zeros, h16 *y, hipStream_t stream)
+                     const h16 *scales, const uint8_t *zeros, h16 *y, int epi, hipStream_t stream)
 {
     if (group % BK == 0) {
         const int tn = (N + 255) / 256;
@@ -516,17 +535,17 @@ int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_
             int rc = sqp_partial_workspace(&part, &bytes, stream);
             if (rc) return rc;
             if ((size_t)p.ksplit * M * N * sizeof(float) > bytes) return SQP_ERR_WORKSPACE;
-            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)p.half, p.ksplit), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, part);
+            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)p.half, p.ksplit), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, part, epi);
             const long total8 = (long)M * N / 8;
-            splitk_reduce_kernel<<<(unsigned)((total8 + 255) / 256), 256, 0, stream>>>(part, total8, (long)M * N, p.ksplit, y);
+            splitk_reduce_kernel<<<(unsigned)((total8 + 255) / 256), 256, 0, stream>>>(part, total8, (long)M * N, p.ksplit, y, epi);
             return sqp_launch_status();
         }
         if (p.full > 0)
-            w4a16_prefill_kernel<MAIN_NT, MAIN_W><<<dim3((unsigned)p.full), MAIN_W * 64, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, nullptr);
+            w4a16_prefill_kernel<MAIN_NT, MAIN_W><<<dim3((unsigned)p.full), MAIN_W * 64, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, nullptr, epi);
         if (p.half > 0)
-            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)p.half), 256, 0, stream>>>(M, N, K, group, (int)p.full, tn, x, packed, scales, zeros, y, nullptr);
+            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)p.half), 256, 0, stream>>>(M, N, K, group, (int)p.full, tn, x, packed, scales, zeros, y, nullptr, epi);
         return sqp_launch_status();
     }
     // group sizes the tiled kernel does not cover
-    return decode_in_row_blocks(M, N, K, group, x, packed, scales, zeros, y, stream);
+    return decode_in_row_blocks(M, N, K, group, x, packed, scales, zeros, y, epi, stream);
 }
