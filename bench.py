@@ -284,6 +284,33 @@ def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, 
     torch.cuda.synchronize()
     extra["alpha_search_21_ms"] = round((time.time() - t0) * 1e3, 1)
     extra["alpha_search_best"] = round(best, 2)
+    # the merged gate/up projection with SiLU(gate) * up fused into the store, against the plain
+    # GEMM on the same weights (8192 -> 44032, M = 16, rotating over the resident layers)
+    Kg, Ng = shapes[2]
+    xg = sqp.smooth_apply_x(activation(16, Kg, 2016), s_first[2])
+    yg = torch.empty((16, Ng), device=dev, dtype=torch.float16)
+    hg = torch.empty((16, Ng // 2), device=dev, dtype=torch.float16)
+    nlg = len(layers)
+    stg = {"i": 0}
+
+    def plain():
+        pq, scq, zq = layers[stg["i"] % nlg][2]
+        stg["i"] += 1
+        sqp.w4a16_gemm(xg, pq, scq, zq, G, out=yg)
+
+    def fused():
+        pq, scq, zq = layers[stg["i"] % nlg][2]
+        stg["i"] += 1
+        sqp.w4a16_gemm_silu_mul(xg, pq, scq, zq, G, out=hg)
+    extra["gate_up_m16_plain_us"] = round(_time(torch, plain, nlg) * 1e6, 1)
+    extra["gate_up_m16_silu_fused_us"] = round(_time(torch, fused, nlg) * 1e6, 1)
+    xn = activation(2048, Kg, 4048)
+    gm = torch.ones(Kg, device=dev, dtype=torch.float16)
+    yn = torch.empty_like(xn)
+    t = _time(torch, lambda: sqp.rmsnorm(xn, gm, 1e-5, out=yn), 5)
+    extra["rmsnorm_2048x%d_us" % Kg] = round(t * 1e6, 1)
+    extra["rmsnorm_gbs"] = round(4.0 * 2048 * Kg / t / 1e9, 1)
+    del xg, yg, hg, xn, yn
     # context: the loss of plain round-to-nearest (no smoothing) on the same layer
     qr = sqp.quantize_pack(w2, G)
     e_rtn = float(sqp.quant_loss(xcal2, w2, xcal2, qr[0], qr[1], qr[2], G)[0])
