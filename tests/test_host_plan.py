@@ -87,3 +87,25 @@ def test_quant_loss_argument_errors(L):
     assert L.sqp_quant_loss_scratch_doubles(512, 8192) == 4 * 64
     assert L.sqp_quant_loss_scratch_doubles(129, 130) == 4
     assert L.sqp_quant_loss_scratch_doubles(0, 8) == 0
+
+
+def test_mlp_entry_argument_errors(L):
+    P = ctypes.c_void_p
+    good, odd, null = P(0x1000), P(0x1008), P(0)
+    f = ctypes.c_float
+    assert L.sqp_rmsnorm(4, 1024, null, good, f(1e-5), good, null) == -1
+    assert L.sqp_rmsnorm(4, 1020, good, good, f(1e-5), good, null) == -2
+    assert L.sqp_rmsnorm(4, 1024, good, good, f(-1.0), good, null) == -4
+    assert L.sqp_rmsnorm(4, 1024, good, good, f(float("nan")), good, null) == -4
+    assert L.sqp_rmsnorm(4, 1024, good, odd, f(1e-5), good, null) == -3
+    assert L.sqp_scale_columns(8, 1020, good, good, good, null) == -2
+    assert L.sqp_scale_columns(8, 1024, good, null, good, null) == -1
+    assert L.sqp_interleave_gate_up(8, 1024, good, good, odd, null) == -3
+    assert L.sqp_interleave_gate_up(0, 1024, good, good, good, null) == -2
+    g = L.sqp_w4a16_gemm_silu_mul
+    assert g(4, 1032, 1024, 128, good, good, good, good, good, null) == -2   # N % 16
+    assert g(4, 1024, 1024, 24, good, good, good, good, good, null) == -2    # group not covered by the fused store
+    assert g(4, 1024, 1152, 192, good, good, good, good, good, null) == -2
+    assert g(4, 1024, 1024, 128, good, good, null, good, good, null) == -1
+    assert L.sqp_transpose_nk(1024, 1020, good, good, null) == -2
+    assert L.sqp_transpose_nk(1024, 1024, good, odd, null) == -3
