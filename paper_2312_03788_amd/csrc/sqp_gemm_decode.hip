@@ -194,26 +194,49 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         // The A fragments come out of the LDS ring with reads written in assembly: the
         // compiler cannot tell which ring slot a direct global->LDS load filled and would wait
         // for every outstanding load; the caller has already waited for this slot.
-        constexpr int XB = MT == 1 ? KSPG : 1;  // k-steps fetched from LDS per batch
+        auto read_x = [&](u32x4 *dst, int ks) {
 #pragma unroll
-        for (int kb = 0; kb < KSPG; kb += XB) {
-            u32x4 xa[XB * MT];
-#pragma unroll
-            for (int kk = 0; kk < XB; kk++)
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++) {
-                    const uint32_t a = xrd[mt] + (uint32_t)(slot * XSTAGE) + (uint32_t)((((kb + kk) * 4 + lk) ^ xsw) * 16);
-                    asm volatile("ds_read_b128 %0, %1" : "=&v"(xa[kk * MT + mt]) : "v"(a) : "memory");
-                }
+            for (int mt = 0; mt < MT; mt++) {
+                const uint32_t a = xrd[mt] + (uint32_t)(slot * XSTAGE) + (uint32_t)(((ks * 4 + lk) ^ xsw) * 16);
+                asm volatile("ds_read_b128 %0, %1" : "=&v"(dst[mt]) : "v"(a) : "memory");
+            }
+        };
+        auto wait_x = [&](u32x4 *dst, int n) {
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-            for (int i = 0; i < XB * MT; i++) asm volatile("" : "+v"(xa[i]));  // no use ahead of the wait
+            for (int i = 0; i < n; i++) asm volatile("" : "+v"(dst[i]));  // no use ahead of the wait
+        };
+        if constexpr (MT == 1) {
+            // one row tile: all k-steps' fragments in one batch (three waves per SIMD hide the rest)
+            u32x4 xa[KSPG];
 #pragma unroll
-            for (int kk = 0; kk < XB; kk++) {
-                const int ks = kb + kk;
+            for (int ks = 0; ks < KSPG; ks++) read_x(&xa[ks], ks);
+            wait_x(xa, KSPG);
+#pragma unroll
+            for (int ks = 0; ks < KSPG; ks++) {
+                const h16x8 a = permute_x(xa[ks]);
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    const h16x8 b = dequant_word(s.w[ks][c], neg_hi[c], neg_lo[c], uc);
+                    accg[0][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, accg[0][c], 0, 0, 0);
+                }
+            }
+        } else {
+            // several row tiles, one or two waves per SIMD: the fragments of the next k-step are
+            // on their way from LDS while this one's MFMAs issue, and the scheduler is told to
+            // put the unpack and permute instructions between the MFMAs (they hide behind them)
+            // instead of in front of them.
+            u32x4 xa[2][MT];
+            read_x(xa[0], 0);
+            wait_x(xa[0], MT);
+#pragma unroll
+            for (int ks = 0; ks < KSPG; ks++) {
+                const int cur = ks & 1, nxt = cur ^ 1;
+                if (ks + 1 < KSPG) read_x(xa[nxt], ks + 1);
+                __builtin_amdgcn_sched_barrier(0);
                 h16x8 a[MT];
 #pragma unroll
-                for (int mt = 0; mt < MT; mt++) a[mt] = permute_x(xa[kk * MT + mt]);
+                for (int mt = 0; mt < MT; mt++) a[mt] = permute_x(xa[cur][mt]);
 #pragma unroll
                 for (int c = 0; c < 4; c++) {
                     const h16x8 b = dequant_word(s.w[ks][c], neg_hi[c], neg_lo[c], uc);
@@ -221,6 +244,13 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
                     for (int mt = 0; mt < MT; mt++)
                         accg[mt][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b, accg[mt][c], 0, 0, 0);
                 }
+#pragma unroll
+                for (int i = 0; i < 4 * MT; i++) {
+                    __builtin_amdgcn_sched_group_barrier(0x002, MT == 2 ? 6 : 3, 0);  // VALU
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // 1 MFMA
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (ks + 1 < KSPG) wait_x(xa[nxt], MT);
             }
         }
 #pragma unroll
