@@ -123,6 +123,12 @@ __global__ void __launch_bounds__(256) apply_w_kernel(long total_oct, int NO, co
 }
 
 // ------------------------------------------------------------------ Eq. 1
+#ifndef SQP_QP_SPLIT128
+#define SQP_QP_SPLIT128 2   // threads sharing a group of 128 rows
+#endif
+#ifndef SQP_QP_SPLIT64
+#define SQP_QP_SPLIT64 1
+#endif
 
 struct GroupParams {
     float d;     // the fp16-rounded step, as float
@@ -171,34 +177,50 @@ __device__ __forceinline__ uint32_t code_fast(float v, float inv, int z, bool &n
     return (uint32_t)q;
 }
 
-// One thread quantises one group of G rows of two adjacent columns; the 2*G weights
-// stay in registers between the min/max pass (exact packed fp16 min/max) and the coding pass.
-// grid: (ceil(N/512), K/G), block 256.
-template <int G>
+// SPLIT adjacent threads quantise one group of G rows of two adjacent columns, G / SPLIT rows
+// each; the weights stay in registers between the min/max pass (exact packed fp16 min/max,
+// combined across the SPLIT lanes by shuffles) and the coding pass.  Fewer rows per thread
+// mean fewer registers and more waves in flight to overlap the loads of one with the
+// arithmetic of another; with SPLIT = 2 a wave still reads whole 128-byte lines (32 column
+// pairs of one row per half).  grid: (ceil(SPLIT * N/2 / 256), K/G), block 256.
+template <int G, int SPLIT>
 __global__ void __launch_bounds__(256) quantize_pack_reg_kernel(int N, const uint32_t *w, uint2 *packed, uint32_t *scales, uint16_t *zeros)
 {
-    const int n2 = blockIdx.x * 256 + threadIdx.x;
+    constexpr int R = G / SPLIT;  // rows per thread
+    static_assert(R % 8 == 0, "whole packed words per thread");
+    const int gid = blockIdx.x * 256 + threadIdx.x;
+    const int n2 = gid / SPLIT, part = gid % SPLIT;
     const int N2 = N >> 1;
+    // N2 * SPLIT is a multiple of SPLIT, so the SPLIT lanes of a group are in or out together
     if (n2 >= N2) return;
     const int t = blockIdx.y;
-    const uint32_t *wp = w + (size_t)t * G * N2 + n2;
-    uint32_t v[G];
+    const uint32_t *wp = w + ((size_t)t * G + (size_t)part * R) * N2 + n2;
+    uint32_t v[R];
 #pragma unroll
-    for (int i = 0; i < G; i++) v[i] = wp[(size_t)i * N2];
+    for (int i = 0; i < R; i++) v[i] = wp[(size_t)i * N2];
     h16x2 mn = __builtin_bit_cast(h16x2, v[0]), mx = mn;
 #pragma unroll
-    for (int i = 1; i < G; i++) {
+    for (int i = 1; i < R; i++) {
         const h16x2 c = __builtin_bit_cast(h16x2, v[i]);
         mn = __builtin_elementwise_min(mn, c);
         mx = __builtin_elementwise_max(mx, c);
     }
-    const GroupParams p0 = group_params((float)mn.x, (float)mx.x), p1 = group_params((float)mn.y, (float)mx.y);
-    scales[(size_t)t * N2 + n2] = (uint32_t)p0.d16 | ((uint32_t)p1.d16 << 16);
-    zeros[(size_t)t * N2 + n2] = (uint16_t)(p0.z | (p1.z << 8));
-    const float inv0 = 1.0f / p0.d, inv1 = 1.0f / p1.d;
-    uint2 *pp = packed + (size_t)t * (G / 8) * N2 + n2;
 #pragma unroll
-    for (int j = 0; j < G / 8; j++) {
+    for (int off = 1; off < SPLIT; off <<= 1) {
+        const h16x2 omn = __builtin_bit_cast(h16x2, __shfl_xor(__builtin_bit_cast(int, mn), off, 64));
+        const h16x2 omx = __builtin_bit_cast(h16x2, __shfl_xor(__builtin_bit_cast(int, mx), off, 64));
+        mn = __builtin_elementwise_min(mn, omn);
+        mx = __builtin_elementwise_max(mx, omx);
+    }
+    const GroupParams p0 = group_params((float)mn.x, (float)mx.x), p1 = group_params((float)mn.y, (float)mx.y);
+    if (part == 0) {
+        scales[(size_t)t * N2 + n2] = (uint32_t)p0.d16 | ((uint32_t)p1.d16 << 16);
+        zeros[(size_t)t * N2 + n2] = (uint16_t)(p0.z | (p1.z << 8));
+    }
+    const float inv0 = 1.0f / p0.d, inv1 = 1.0f / p1.d;
+    uint2 *pp = packed + ((size_t)t * (G / 8) + (size_t)part * (R / 8)) * N2 + n2;
+#pragma unroll
+    for (int j = 0; j < R / 8; j++) {
         uint32_t w0 = 0, w1 = 0;
         bool near_tie = false;
 #pragma unroll
@@ -361,14 +383,15 @@ extern "C" int sqp_quantize_pack(int N, int K, int group, const void *w, uint32_
     if (sqp_misaligned(w) || sqp_misaligned(packed) || sqp_misaligned(scales) || sqp_misaligned(zeros)) return SQP_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     dim3 grid((N / 2 + 255) / 256, K / group);
+    dim3 grid2((N + 255) / 256, K / group);  // two threads per column pair
     const uint32_t *wp = (const uint32_t *)w;
     uint2 *pp = (uint2 *)packed;
     uint32_t *sp = (uint32_t *)scales;
     uint16_t *zp = (uint16_t *)zeros;
     switch (group) {
-        case 32: quantize_pack_reg_kernel<32><<<grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
-        case 64: quantize_pack_reg_kernel<64><<<grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
-        case 128: quantize_pack_reg_kernel<128><<<grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
+        case 32: quantize_pack_reg_kernel<32, 1><<<grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
+        case 64: quantize_pack_reg_kernel<64, SQP_QP_SPLIT64><<<SQP_QP_SPLIT64 == 2 ? grid2 : grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
+        case 128: quantize_pack_reg_kernel<128, SQP_QP_SPLIT128><<<SQP_QP_SPLIT128 == 2 ? grid2 : grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
         default: quantize_pack_any_kernel<<<grid, 256, 0, st>>>(N, group, wp, pp, sp, zp); break;
     }
     return sqp_launch_status();
