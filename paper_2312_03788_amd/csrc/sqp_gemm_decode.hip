@@ -119,17 +119,22 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     const uint32_t voff_w = (uint32_t)(lk * N + ncol) * 4u;
     const int wrow_stride = N;
     const uint32_t voff_s = (uint32_t)ncol * 2u, voff_z = (uint32_t)ncol;
-    auto issue_w = [&](Stage &s, int g) {
+    // The loading side walks the chunks with wave-uniform byte pointers stepped by constant
+    // strides (scalar adds, no multiplies or divisions in the loop).
+    const long wstep1 = (long)wrow_stride * 16;                 // one k-step: 4 packed rows, in bytes
+    const unsigned char *wq = reinterpret_cast<const unsigned char *>(packed) + (long)g0 * KSPG * wstep1;
+    const unsigned char *sq = reinterpret_cast<const unsigned char *>(scales) + (long)(g0 / cpg) * N * 2;
+    const unsigned char *zq = zeros + (long)(g0 / cpg) * N;
+    const unsigned char *xq = reinterpret_cast<const unsigned char *>(x) + (long)g0 * (64 * KSPG);
+    int gi = g0, kin = g0 % cpg;                                 // chunk being issued, its position in its group
+    auto issue_w = [&](Stage &s) {
 #pragma unroll
         for (int ks = 0; ks < KSPG; ks++) {
-            const uint32_t *base = packed + (size_t)(g * KSPG + ks) * 4 * wrow_stride;  // wave-uniform
+            const unsigned char *base = wq + ks * wstep1;        // wave-uniform
             asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
         }
-        const int gs = g / cpg;  // quantisation group of this chunk
-        const h16 *sbase = scales + (size_t)gs * N;
-        const uint8_t *zbase = zeros + (size_t)gs * N;
-        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sbase) : "memory");
-        asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zbase) : "memory");
+        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sq) : "memory");
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zq) : "memory");
     };
     // wait until at most `after` loads are outstanding, then tie the stage's registers to the
     // wait so that no use of them is scheduled ahead of it
@@ -155,12 +160,11 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         const int rowc = row < M ? row : M - 1;
         xoff[i] = (uint32_t)rowc * (uint32_t)K * 2u + (uint32_t)((xpp ^ (row % PP)) * 16);
     }
-    auto issue_x = [&](int slot, int g) {
-        const h16 *base = x + (size_t)g * (32 * KSPG);  // wave-uniform
+    auto issue_x = [&](int slot) {
 #pragma unroll
         for (int i = 0; i < OX; i++) {
             const int b = (wave + i * NW) % XBLOCKS;
-            const unsigned char *src = reinterpret_cast<const unsigned char *>(base) + xoff[i];
+            const unsigned char *src = xq + xoff[i];
             unsigned char *dst = xring + slot * XSTAGE + b * 1024;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
@@ -272,13 +276,25 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // traffic) and such chunks enter the sum with a step of 0.  Every iteration thus issues the
     // same OX + OW loads, and since loads complete in issue order "at most (P-1)(OX + OW) loads
     // outstanding" means all but the last P-1 iterations' have landed.
-    const int glast = g1 > g0 ? g1 - 1 : (g0 < chunks ? g0 : chunks - 1);
-    auto gc = [&](int g) { return g < glast ? g : glast; };  // past the range: this workgroup's own last chunk again (a cache hit)
+    // past the range the pointers stop: this workgroup's own last chunk again (a cache hit)
+    const int glast = g1 > g0 ? g1 - 1 : g0;
+    auto advance = [&]() {
+        const bool more = gi < glast;
+        gi += more ? 1 : 0;
+        wq += more ? KSPG * wstep1 : 0;
+        xq += more ? 64 * KSPG : 0;
+        kin += more ? 1 : 0;
+        const bool wrap = kin == cpg;
+        kin = wrap ? 0 : kin;
+        sq += wrap ? (long)N * 2 : 0;
+        zq += wrap ? (long)N : 0;
+    };
     Stage st[D];
 #pragma unroll
     for (int j = 0; j < P; j++) {
-        issue_x(j, gc(g0 + j));
-        issue_w(st[j], gc(g0 + j));
+        issue_x(j);
+        issue_w(st[j]);
+        advance();
     }
     int slot = 0;  // ring slot of chunk g
     const int nblk = (g1 - g0 + D - 1) / D;
@@ -290,8 +306,9 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
             landed(st[d], std::integral_constant<int, (P - 1) * (OX + OW)>());
             asm volatile("s_barrier" ::: "memory");
             const int fill = slot >= 1 ? slot - 1 : XD - 1;  // (slot + P) % XD
-            issue_x(fill, gc(gg + P));
-            issue_w(st[(d + P) % D], gc(gg + P));
+            issue_x(fill);
+            issue_w(st[(d + P) % D]);
+            advance();
             compute(st[d], slot, gg < g1);
             slot = slot + 1 == XD ? 0 : slot + 1;
         }
