@@ -309,7 +309,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
             issue_x(fill);
             issue_w(st[(d + P) % D]);
             advance();
-            compute(st[d], slot, gg < g1);
+            if (gg < g1) compute(st[d], slot, true);  // padded iterations only keep the load counts in step
             slot = slot + 1 == XD ? 0 : slot + 1;
         }
     }
@@ -507,22 +507,30 @@ struct Plan {
 
 // Strips per workgroup and K split, from sweeps on Code Llama shapes.  Four strips per
 // workgroup share one copy of the activations.  Narrow layers (up to 128 column tiles) run
-// best with one workgroup per compute unit (256 in all), each walking a long K range; wider
-// ones with two to three workgroups per unit.  More splits than that cost more in fp32
-// partial tiles than the extra parallelism brings.
+// best with at most one workgroup per compute unit (256 in all; one more than that and a
+// second round of workgroups starts, which costs 20 % and more), each walking a long K
+// range; wider ones with two to three workgroups per unit.  More splits than that cost
+// more in fp32 partial tiles than the extra parallelism brings.  Where a narrow layer is
+// also short in K, so that 256 four-strip workgroups would get fewer than eight chunks
+// each, two strips per workgroup and half the split keep the pipelines longer.
 Plan make_plan(int M, int N, int K, int chunk)
 {
     const int chunks = K / chunk;
-    Plan p;
-    p.nw = 4;
-    const int tiles = (N + 64 * p.nw - 1) / (64 * p.nw);
-    const int target = tiles <= 128 ? 256 : 704;
-    int want = (target + tiles / 2) / tiles;
     int max_split = chunks / 4;  // at least four chunks per workgroup
     if (max_split < 1) max_split = 1;
-    if (want > max_split) want = max_split;
-    if (want < 1) want = 1;
-    p.split = want;
+    auto split_for = [&](int tiles) {
+        int want = tiles <= 128 ? 256 / tiles : (704 + tiles / 2) / tiles;
+        if (want > max_split) want = max_split;
+        return want < 1 ? 1 : want;
+    };
+    Plan p;
+    p.nw = 4;
+    const int tiles4 = (N + 255) / 256;
+    p.split = split_for(tiles4);
+    if (tiles4 <= 24 && chunks < 8 * (256 / tiles4)) {
+        p.nw = 2;
+        p.split = split_for((N + 127) / 128);
+    }
     (void)M;
     return p;
 }
