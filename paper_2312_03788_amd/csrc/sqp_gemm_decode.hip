@@ -59,6 +59,9 @@ __device__ __forceinline__ void store_row4(h16 *y, int m, int N, int n, int epi,
     }
 }
 
+// Split-K tickets: one per 128-byte line (atomics on one line are served one after the other).
+constexpr int TICKET_STRIDE = 32;
+
 // MT: 16-row tiles of x (M <= 16*MT).  NW: waves (64-column strips) per workgroup.
 // KSPG: k-steps (of 32) per chunk; a quantisation group is cpg chunks (cpg = 1 unless the
 // group is a multiple of 128 above 128).
@@ -313,22 +316,27 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
             slot = slot + 1 == XD ? 0 : slot + 1;
         }
     }
-    // Drain the clamped look-ahead loads.  Their destination registers are dead by now as far
-    // as the compiler can tell, but the hardware still writes them when the data arrives: the
-    // empty uses below keep every stage allocated until the wait has completed, so that
-    // nothing else is placed in those registers while a load is in flight.
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // The clamped look-ahead loads are still in flight here.  Their destination registers are
+    // dead by now as far as the compiler can tell, but the hardware still writes them when the
+    // data arrives: `drain` waits for everything outstanding and its empty uses keep every stage
+    // allocated until then, so that nothing else is placed in those registers while a load is in
+    // flight.  It runs after the epilogue's stores have been issued (they only read the
+    // accumulators), so that one wait covers both.
+    auto drain = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int j = 0; j < D; j++) {
+        for (int j = 0; j < D; j++) {
 #pragma unroll
-        for (int ks = 0; ks < KSPG; ks++) asm volatile("" ::"v"(st[j].w[ks]));
-        asm volatile("" ::"v"(st[j].sc));
-        asm volatile("" ::"v"(st[j].zr));
-    }
+            for (int ks = 0; ks < KSPG; ks++) asm volatile("" ::"v"(st[j].w[ks]));
+            asm volatile("" ::"v"(st[j].sc));
+            asm volatile("" ::"v"(st[j].zr));
+        }
+    };
 
     // ---- epilogue.  Accumulator tile t, register r of a lane: row mt*16 + 4*(lane/16) + r,
     // column n0 + 4*(lane%16) + t.
     const int nout = n0 + 4 * lc;
+    drain();
     if (split == 1) {
         if (nout < N) {
 #pragma unroll
@@ -349,18 +357,18 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // is the ticket taken.  Layout: [tile][split][wave][Q][lane][4] floats (each instruction
     // moves 1 KB contiguous per wave).
     constexpr int Q = REGS / 4;                         // 16-byte pieces per lane
-    constexpr int SB = MT == 1 ? 4 : (MT == 2 ? 2 : 1);  // partials fetched per round trip
+    constexpr int SB = 32 / Q;                          // partials fetched per round trip (128 registers)
     {
         float *mine = ws.partial + (((size_t)tile * split + sidx) * NW + wave) * (64 * REGS) + lane * 4;
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
 #pragma unroll
             for (int t = 0; t < 4; t++)
-                asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(mine + (mt * 4 + t) * 256), "v"(acc[mt][t]) : "memory");
+                asm volatile("global_store_dwordx4 %0, %1, off offset:%2 sc1" ::"v"(mine + mt * 1024), "v"(acc[mt][t]), "n"(t * 1024) : "memory");
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     __syncthreads();
-    if (threadIdx.x == 0) ticket_s = __hip_atomic_fetch_add(&ws.tickets[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) ticket_s = __hip_atomic_fetch_add(&ws.tickets[tile * TICKET_STRIDE], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket_s != (unsigned)(split - 1)) return;
     {
@@ -401,7 +409,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         }
     }
     if (threadIdx.x == 0)  // ready for the next launch on this stream
-        __hip_atomic_store(&ws.tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&ws.tickets[tile * TICKET_STRIDE], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Any group size that is a multiple of 8 and any M: one thread per output element.
@@ -434,7 +442,7 @@ w4a16_generic_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
 // ---------------------------------------------------------------- workspace
 
 constexpr size_t WS_PARTIAL_BYTES = (size_t)128 << 20;  // fp32 partial sums (decode split-K tiles, tiled-path K parts)
-constexpr int WS_TICKETS = 1 << 16;
+constexpr int WS_TICKETS = 1 << 17;
 Workspace g_ws[16] = {};
 
 __global__ void zero_tickets_kernel(unsigned *t, int n)
@@ -491,7 +499,7 @@ int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t
     Workspace ws = {nullptr, nullptr};
     if (split > 1) {
         const size_t tile_bytes = (size_t)NW * MT * 16 * 64 * sizeof(float);
-        if (tiles > WS_TICKETS || (size_t)tiles * split * tile_bytes > WS_PARTIAL_BYTES) split = 1;
+        if (tiles * TICKET_STRIDE > WS_TICKETS || (size_t)tiles * split * tile_bytes > WS_PARTIAL_BYTES) split = 1;
     }
     if (split > 1) {
         int rc = get_workspace(&ws, st);
