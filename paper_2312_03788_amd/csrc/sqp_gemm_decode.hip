@@ -362,9 +362,11 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         float *mine = ws.partial + (((size_t)tile * split + sidx) * NW + wave) * (64 * REGS) + lane * 4;
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
+            if (mt * 16 + 4 * lk < M) {  // lanes whose four rows are all past M have nothing to hand over
 #pragma unroll
-            for (int t = 0; t < 4; t++)
-                asm volatile("global_store_dwordx4 %0, %1, off offset:%2 sc1" ::"v"(mine + mt * 1024), "v"(acc[mt][t]), "n"(t * 1024) : "memory");
+                for (int t = 0; t < 4; t++)
+                    asm volatile("global_store_dwordx4 %0, %1, off offset:%2 sc1" ::"v"(mine + mt * 1024), "v"(acc[mt][t]), "n"(t * 1024) : "memory");
+            }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     __syncthreads();
@@ -374,6 +376,14 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     {
         const float *base = ws.partial + (((size_t)tile * split) * NW + wave) * (64 * REGS) + lane * 4;
         const size_t sstride = (size_t)NW * 64 * REGS;
+        // Lanes whose four rows are all past M stored nothing and their sums are never written:
+        // they re-read the first 16 lanes' pieces (the same cache lines) instead of lines of
+        // their own, which for M <= 4 cuts the bytes the last arrival pulls in to a quarter.
+        // (The loads stay unconditional: every lane's destination registers must be written by
+        // exactly these instructions for the wait below to cover them.)
+        int dead[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) dead[mt] = mt * 16 + 4 * lk < M ? 0 : -64 * lk;
         f32x4 sum[Q];
 #pragma unroll
         for (int q = 0; q < Q; q++) sum[q] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -384,7 +394,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
                 if (s0 + j < split) {
 #pragma unroll
                     for (int q = 0; q < Q; q++)
-                        asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(tmp[j][q]) : "v"(base + (size_t)(s0 + j) * sstride + q * 256) : "memory");
+                        asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(tmp[j][q]) : "v"(base + (size_t)(s0 + j) * sstride + q * 256 + dead[q / 4]) : "memory");
                 }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
