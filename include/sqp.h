@@ -16,7 +16,7 @@
  *   - Return value: SQP_OK (0), or a negative error code, in which case nothing was
  *     enqueued.  sqp_status_string() names a code.
  *   - Shape rules: M, N, K > 0; N % 8 == 0; K % 8 == 0; group % 8 == 0, group >= 8,
- *     K % group == 0.
+ *     K % group == 0; every tensor has fewer than 2^31 elements.
  *
  * Storage format of a quantised weight (what sqp_quantize_pack writes and
  * sqp_dequantize / sqp_w4a16_gemm read):

@@ -86,6 +86,7 @@ static int gemm_entry(int M, int N, int K, int group, const void *x, const uint3
     if (M <= 0) return SQP_ERR_SHAPE;
     int rc = sqp_check_quant_shape(N, K, group);
     if (rc) return rc;
+    if (sqp_too_big(M, K) || sqp_too_big(M, N)) return SQP_ERR_SHAPE;
     if (sqp_misaligned(x) || sqp_misaligned(packed) || sqp_misaligned(scales) || sqp_misaligned(zeros) || sqp_misaligned(y))
         return SQP_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;

@@ -14,9 +14,14 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 static inline bool sqp_misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// Size limit of every entry point: a tensor has fewer than 2^31 elements (the kernels keep
+// per-lane offsets in 32 bits).
+static inline bool sqp_too_big(long rows, long cols) { return rows * cols >= (1L << 31); }
+
 static inline int sqp_check_quant_shape(int N, int K, int group)
 {
     if (N <= 0 || K <= 0 || group < 8) return SQP_ERR_SHAPE;
+    if (sqp_too_big(K, N)) return SQP_ERR_SHAPE;
     if ((N % 8) || (K % 8) || (group % 8) || (K % group)) return SQP_ERR_SHAPE;
     return SQP_OK;
 }

@@ -303,6 +303,7 @@ extern "C" int sqp_smooth_scales(int T, int K, int N, float alpha, const void *x
 {
     if (!x_cal || !w || !s) return SQP_ERR_NULL;
     if (T <= 0 || K <= 0 || N <= 0 || (K % 8) || (N % 8)) return SQP_ERR_SHAPE;
+    if (sqp_too_big(T, K) || sqp_too_big(K, N)) return SQP_ERR_SHAPE;
     if (sqp_misaligned(x_cal) || sqp_misaligned(w) || sqp_misaligned(s)) return SQP_ERR_ALIGN;
     if (!(alpha >= 0.0f && alpha <= 1.0f)) return SQP_ERR_ARG;
     hipStream_t st = (hipStream_t)stream;
@@ -317,7 +318,7 @@ extern "C" int sqp_smooth_scales(int T, int K, int N, float alpha, const void *x
 extern "C" int sqp_smooth_apply_x(int M, int K, const void *x, const float *s, void *x_out, void *stream)
 {
     if (!x || !s || !x_out) return SQP_ERR_NULL;
-    if (M <= 0 || K <= 0 || (K % 8)) return SQP_ERR_SHAPE;
+    if (M <= 0 || K <= 0 || (K % 8) || sqp_too_big(M, K)) return SQP_ERR_SHAPE;
     if (sqp_misaligned(x) || sqp_misaligned(s) || sqp_misaligned(x_out)) return SQP_ERR_ALIGN;
     long total = (long)M * (K / 8);
     apply_x_kernel<<<(unsigned)((total + 255) / 256), 256, 0, (hipStream_t)stream>>>(total, K / 8, (const uint4 *)x, (const float4 *)s, (uint4 *)x_out);
@@ -327,7 +328,7 @@ extern "C" int sqp_smooth_apply_x(int M, int K, const void *x, const float *s, v
 extern "C" int sqp_smooth_apply_w(int K, int N, const void *w, const float *s, void *w_out, void *stream)
 {
     if (!w || !s || !w_out) return SQP_ERR_NULL;
-    if (K <= 0 || N <= 0 || (N % 8)) return SQP_ERR_SHAPE;
+    if (K <= 0 || N <= 0 || (N % 8) || sqp_too_big(K, N)) return SQP_ERR_SHAPE;
     if (sqp_misaligned(w) || sqp_misaligned(s) || sqp_misaligned(w_out)) return SQP_ERR_ALIGN;
     long total = (long)K * (N / 8);
     apply_w_kernel<<<(unsigned)((total + 255) / 256), 256, 0, (hipStream_t)stream>>>(total, N / 8, (const uint4 *)w, s, (uint4 *)w_out);
@@ -367,7 +368,7 @@ __global__ void __launch_bounds__(256) transpose_nk_kernel(int N, int K, const h
 extern "C" int sqp_transpose_nk(int N, int K, const void *w_nk, void *w_kn, void *stream)
 {
     if (!w_nk || !w_kn) return SQP_ERR_NULL;
-    if (N <= 0 || K <= 0 || (N % 8) || (K % 8)) return SQP_ERR_SHAPE;
+    if (N <= 0 || K <= 0 || (N % 8) || (K % 8) || sqp_too_big(K, N)) return SQP_ERR_SHAPE;
     if (sqp_misaligned(w_nk) || sqp_misaligned(w_kn)) return SQP_ERR_ALIGN;
     if ((N + 63) / 64 > 65535) return SQP_ERR_SHAPE;
     transpose_nk_kernel<<<dim3((K + 63) / 64, (N + 63) / 64), 256, 0, (hipStream_t)stream>>>(N, K, (const h16 *)w_nk, (h16 *)w_kn);

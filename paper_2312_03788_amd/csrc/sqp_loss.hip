@@ -174,6 +174,7 @@ extern "C" int sqp_quant_loss(int M, int N, int K, int group, const void *x, con
     if (M <= 0) return SQP_ERR_SHAPE;
     int rc = sqp_check_quant_shape(N, K, group);
     if (rc) return rc;
+    if (sqp_too_big(M, K) || sqp_too_big(M, N)) return SQP_ERR_SHAPE;
     if (sqp_misaligned(x) || sqp_misaligned(w) || sqp_misaligned(x_hat) || sqp_misaligned(packed) ||
         sqp_misaligned(scales) || sqp_misaligned(zeros))
         return SQP_ERR_ALIGN;

@@ -93,7 +93,7 @@ __global__ void __launch_bounds__(256) interleave_kernel(long total_oct, int IO,
 extern "C" int sqp_rmsnorm(int M, int H, const void *x, const void *gamma, float eps, void *y, void *stream)
 {
     if (!x || !gamma || !y) return SQP_ERR_NULL;
-    if (M <= 0 || H <= 0 || (H % 8)) return SQP_ERR_SHAPE;
+    if (M <= 0 || H <= 0 || (H % 8) || sqp_too_big(M, H)) return SQP_ERR_SHAPE;
     if (!(eps >= 0.0f) || !(eps < 1.0f)) return SQP_ERR_ARG;
     if (sqp_misaligned(x) || sqp_misaligned(gamma) || sqp_misaligned(y)) return SQP_ERR_ALIGN;
     rmsnorm_kernel<<<(unsigned)M, 256, 0, (hipStream_t)stream>>>(H / 8, 1.0f / (float)H, eps, (const uint4 *)x, (const uint4 *)gamma, (uint4 *)y);
@@ -103,7 +103,7 @@ extern "C" int sqp_rmsnorm(int M, int H, const void *x, const void *gamma, float
 extern "C" int sqp_scale_columns(int K, int N, const void *w, const float *s, void *w_out, void *stream)
 {
     if (!w || !s || !w_out) return SQP_ERR_NULL;
-    if (K <= 0 || N <= 0 || (N % 8)) return SQP_ERR_SHAPE;
+    if (K <= 0 || N <= 0 || (N % 8) || sqp_too_big(K, N)) return SQP_ERR_SHAPE;
     if (sqp_misaligned(w) || sqp_misaligned(s) || sqp_misaligned(w_out)) return SQP_ERR_ALIGN;
     const long total = (long)K * (N / 8);
     scale_columns_kernel<<<(unsigned)((total + 255) / 256), 256, 0, (hipStream_t)stream>>>(total, N / 8, (const uint4 *)w, (const float4 *)s, (uint4 *)w_out);
@@ -113,7 +113,7 @@ extern "C" int sqp_scale_columns(int K, int N, const void *w, const float *s, vo
 extern "C" int sqp_interleave_gate_up(int K, int I, const void *w_gate, const void *w_up, void *w_out, void *stream)
 {
     if (!w_gate || !w_up || !w_out) return SQP_ERR_NULL;
-    if (K <= 0 || I <= 0 || (I % 8)) return SQP_ERR_SHAPE;
+    if (K <= 0 || I <= 0 || (I % 8) || sqp_too_big(K, 2L * I)) return SQP_ERR_SHAPE;
     if (sqp_misaligned(w_gate) || sqp_misaligned(w_up) || sqp_misaligned(w_out)) return SQP_ERR_ALIGN;
     const long total = (long)K * (I / 8);
     interleave_kernel<<<(unsigned)((total + 255) / 256), 256, 0, (hipStream_t)stream>>>(total, I / 8, (const uint4 *)w_gate, (const uint4 *)w_up, (uint4 *)w_out);

@@ -57,6 +57,16 @@ def test_argument_errors(L):
     assert s(8, 1021, 1024, ctypes.c_float(0.5), good, good, good, null) == -2
     assert L.sqp_smooth_apply_x(4, 1024, good, good, odd, null) == -3
     assert L.sqp_smooth_apply_w(1024, 1020, good, good, good, null) == -2
+    # size limit: every tensor has fewer than 2^31 elements (nothing is launched for these)
+    assert g(4, 1 << 16, 1 << 15, 128, good, good, good, good, good, null) == -2       # K * N = 2^31
+    assert g(1 << 15, 1024, 1 << 16, 128, good, good, good, good, good, null) == -2    # M * K = 2^31
+    assert g(1 << 16, 1 << 15, 64, 64, good, good, good, good, good, null) == -2       # M * N = 2^31
+    assert q(1 << 16, 1 << 15, 128, good, good, good, good, null) == -2
+    assert d(1 << 16, 1 << 15, 128, good, good, good, good, null) == -2
+    assert s(1 << 16, 1 << 15, 8, ctypes.c_float(0.5), good, good, good, null) == -2
+    assert L.sqp_smooth_apply_x(1 << 16, 1 << 15, good, good, good, null) == -2
+    assert L.sqp_rmsnorm(1 << 16, 1 << 15, good, good, ctypes.c_float(1e-5), good, null) == -2
+    assert L.sqp_transpose_nk(1 << 16, 1 << 15, good, good, null) == -2
 
 
 def test_product_does_not_import_oracle():
