@@ -317,6 +317,43 @@ def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, 
     e_best = min(v for _, v in curve)
     extra["loss_rtn_over_best_alpha"] = round(e_rtn / e_best, 2)
     del w2, xcal2, xh2, q2, qr
+    # the other two model sizes the configurations name (context: same kernel, same plan rule),
+    # M = 16 sweeps over random codes/steps/zero points, replayed from a graph like the headline
+    by_model = {}
+    for model in ("7b", "13b"):
+        if model not in wl.MODEL_SHAPES:
+            continue
+        mshapes, nl = wl.MODEL_SHAPES[model], wl.MODEL_LAYERS[model]
+        gen.manual_seed(77)
+        mlayers = []
+        for _ in range(nl):
+            per = []
+            for (Km, Nm) in mshapes:
+                p = torch.randint(-2**31, 2**31 - 1, (Km // 8, Nm), dtype=torch.int32, device=dev, generator=gen)
+                sc = (torch.rand((Km // G, Nm), device=dev, generator=gen) * 0.004 + 0.003).half()
+                z = torch.randint(0, 16, (Km // G, Nm), dtype=torch.uint8, device=dev, generator=gen)
+                per.append((p, sc, z))
+            mlayers.append(per)
+        mx = [torch.randn((16, Km), device=dev, generator=gen, dtype=torch.float32).half() for (Km, Nm) in mshapes]
+        my = [torch.empty((16, Nm), device=dev, dtype=torch.float16) for (Km, Nm) in mshapes]
+
+        def msweep():
+            for per in mlayers:
+                for si, (p, sc, z) in enumerate(per):
+                    sqp.w4a16_gemm(mx[si], p, sc, z, G, out=my[si])
+        msweep()
+        torch.cuda.synchronize()
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            mgraph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(mgraph, stream=stream):
+                msweep()
+        torch.cuda.synchronize()
+        t = _time(torch, mgraph.replay, 5)
+        b = nl * sum(wl.algorithmic_bytes(16, Nm, Km, G) for (Km, Nm) in mshapes)
+        by_model[model] = {"gbs": round(b / t / 1e9, 1), "us_per_launch": round(t * 1e6 / (nl * len(mshapes)), 2)}
+        del mgraph, mlayers, mx, my
+    extra["decode_m16_other_models"] = by_model
     # context only (never a target): dense fp16 x fp16 GEMM of the vendor library through
     # torch.matmul at the same shapes, weights rotating over >= 1.5 GB so that they stream from HBM
     dense = {}
