@@ -18,7 +18,8 @@
 //     (1024 + Z or 64 + Z) is subtracted with a packed fp16 add, which is exact.
 //   - The MFMA accumulates one chunk in fp32, then the step Delta (a per-lane scalar in the
 //     16x16 accumulator layout: column = lane % 16) scales it into the running sum:
-//     sum_k x (q - Z) Delta = Delta * sum_k x (q - Z).
+//     sum_k x (q - Z) Delta = Delta * sum_k x (q - Z).  (The 64-row variant multiplies the
+//     unpacked weights by Delta instead, which is less vector work there.)
 //   - Weight loads and all waits are written in assembly: D - 1 chunks of weights stay in
 //     flight per wave while one is consumed, and the compiler's conservative waits (it cannot
 //     tell ring slots apart) would serialise that.
@@ -84,6 +85,10 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     constexpr int XSTAGE = XBLOCKS * 1024;
     constexpr int OX = (XBLOCKS + NW - 1) / NW;  // direct loads per wave per chunk
     constexpr int OW = KSPG + 2;                 // weight-side loads per wave per chunk
+    // With four row tiles the per-chunk scaling of 64 accumulator registers costs more vector
+    // work than multiplying the unpacked weights by the step (4 packed multiplies per word, as
+    // in the tiled kernel), so that variant accumulates fp16(w_hat) products directly.
+    constexpr bool SCALED_B = MT == 4;
     static_assert((P - 1) * (OX + OW) < 64, "vmcnt field");
     __shared__ __attribute__((aligned(1024))) unsigned char xring[XD * XSTAGE];
     __shared__ unsigned ticket_s;
@@ -188,7 +193,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         for (int mt = 0; mt < MT; mt++)
 #pragma unroll
             for (int t = 0; t < 4; t++) accg[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-        h16x2 neg_hi[4], neg_lo[4];
+        h16x2 neg_hi[4], neg_lo[4], delta2[4];
         float delta[4];
 #pragma unroll
         for (int c = 0; c < 4; c++) {
@@ -196,7 +201,9 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
             neg_hi[c] = neg_hi_of(z);
             neg_lo[c] = neg_lo_of(z);
             const h16x2 sv = __builtin_bit_cast(h16x2, (uint32_t)s.sc[c >> 1]);
-            delta[c] = live ? (float)((c & 1) ? sv.y : sv.x) : 0.f;
+            const h16 d16 = (c & 1) ? sv.y : sv.x;
+            delta[c] = live ? (float)d16 : 0.f;
+            delta2[c] = h16x2{d16, d16};
         }
         // The A fragments come out of the LDS ring with reads written in assembly: the
         // compiler cannot tell which ring slot a direct global->LDS load filled and would wait
@@ -246,26 +253,35 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
                 for (int mt = 0; mt < MT; mt++) a[mt] = permute_x(xa[cur][mt]);
 #pragma unroll
                 for (int c = 0; c < 4; c++) {
-                    const h16x8 b = dequant_word(s.w[ks][c], neg_hi[c], neg_lo[c], uc);
+                    if constexpr (SCALED_B) {
+                        const h16x8 b = dequant_word_scaled(s.w[ks][c], neg_hi[c], neg_lo[c], delta2[c], uc);
 #pragma unroll
-                    for (int mt = 0; mt < MT; mt++)
-                        accg[mt][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b, accg[mt][c], 0, 0, 0);
+                        for (int mt = 0; mt < MT; mt++)
+                            acc[mt][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b, acc[mt][c], 0, 0, 0);
+                    } else {
+                        const h16x8 b = dequant_word(s.w[ks][c], neg_hi[c], neg_lo[c], uc);
+#pragma unroll
+                        for (int mt = 0; mt < MT; mt++)
+                            accg[mt][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b, accg[mt][c], 0, 0, 0);
+                    }
                 }
 #pragma unroll
                 for (int i = 0; i < 4 * MT; i++) {
-                    __builtin_amdgcn_sched_group_barrier(0x002, MT == 2 ? 6 : 3, 0);  // VALU
+                    __builtin_amdgcn_sched_group_barrier(0x002, MT == 2 ? 6 : (SCALED_B ? 4 : 3), 0);  // VALU
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // 1 MFMA
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (ks + 1 < KSPG) wait_x(xa[nxt], MT);
             }
         }
+        if constexpr (!SCALED_B) {
 #pragma unroll
-        for (int mt = 0; mt < MT; mt++)
+            for (int mt = 0; mt < MT; mt++)
 #pragma unroll
-            for (int t = 0; t < 4; t++)
+                for (int t = 0; t < 4; t++)
 #pragma unroll
-                for (int r = 0; r < 4; r++) acc[mt][t][r] = fmaf(delta[t], accg[mt][t][r], acc[mt][t][r]);
+                    for (int r = 0; r < 4; r++) acc[mt][t][r] = fmaf(delta[t], accg[mt][t][r], acc[mt][t][r]);
+        }
     };
 
     // Software pipeline over the chunk range, P = D - 1 chunks ahead.  Iteration g: wait for
@@ -365,7 +381,10 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
             if (mt * 16 + 4 * lk < M) {  // lanes whose four rows are all past M have nothing to hand over
 #pragma unroll
                 for (int t = 0; t < 4; t++)
-                    asm volatile("global_store_dwordx4 %0, %1, off offset:%2 sc1" ::"v"(mine + mt * 1024), "v"(acc[mt][t]), "n"(t * 1024) : "memory");
+                    // (the s_nop: a store of more than 8 bytes reads its data registers up to two wait
+                    // states after issue, and the compiler, which does not look inside asm statements,
+                    // may reuse them for the next copy out of the accumulator registers right away)
+                    asm volatile("global_store_dwordx4 %0, %1, off offset:%2 sc1\n\ts_nop 1" ::"v"(mine + mt * 1024), "v"(acc[mt][t]), "n"(t * 1024) : "memory");
             }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
