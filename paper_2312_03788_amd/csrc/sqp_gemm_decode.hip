@@ -568,7 +568,10 @@ Plan make_plan(int M, int N, int K, int chunk)
         p.nw = 2;
         p.split = split_for((N + 127) / 128);
     }
-    (void)M;
+    // More than 32 rows: the fp32 partial tiles are four times as large and the last arrival's
+    // fetch of them is bound by its one compute unit, so the same waves are grouped into twice as
+    // many workgroups of two strips (half the bytes per fetching unit; 1-6 % faster at M = 64).
+    if (M > 32 && p.nw == 4 && p.split > 1) p.nw = 2;
     return p;
 }
 

@@ -57,6 +57,16 @@ def test_decode_plan_34b_values(L):
     assert got == {(8192, 10240): (4, 6), (8192, 8192): (4, 8), (8192, 44032): (4, 4), (22016, 8192): (4, 8)}
 
 
+def test_decode_plan_many_rows(L):
+    """More than 32 rows: two strips per workgroup, the split of the 16-row plan."""
+    for (K, N) in wl.MODEL_SHAPES["34b"]:
+        nw16, split16, _ = _decode_plan(L, 16, N, K, 128)
+        assert _decode_plan(L, 32, N, K, 128)[:2] == (nw16, split16)
+        assert _decode_plan(L, 64, N, K, 128)[:2] == (2, split16)
+    assert _decode_plan(L, 64, 512, 256, 128)[:2] == (2, 1)            # short K: no split
+    assert _decode_plan(L, 64, 65536, 256, 128)[:2] == (4, 1)
+
+
 def test_decode_plan_small_model_values(L):
     """Shapes where the sweeps found the four-strip, rounded-up plan 10-25 % off the best."""
     assert _decode_plan(L, 16, 4096, 4096, 128)[:2] == (2, 8)      # narrow and short: two strips
