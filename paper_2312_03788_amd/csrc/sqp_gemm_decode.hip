@@ -290,11 +290,11 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // more), issue x(g+P) and the weights of chunk g+P into that slot and the stage just freed
     // (stage index static: the loop is unrolled by D), consume chunk g.  The pipeline is primed
     // by issuing chunks g0 .. g0+P-1.
-    // The loop body is free of branches: the chunk count is rounded up to a multiple of D,
-    // loads past the range are clamped to the range's last chunk (cache hits, no extra HBM
-    // traffic) and such chunks enter the sum with a step of 0.  Every iteration thus issues the
-    // same OX + OW loads, and since loads complete in issue order "at most (P-1)(OX + OW) loads
-    // outstanding" means all but the last P-1 iterations' have landed.
+    // The loading side of the loop body is free of branches: the chunk count is rounded up to a
+    // multiple of D and loads past the range are clamped to the range's last chunk (cache hits,
+    // no extra HBM traffic); only the arithmetic of such padded iterations is skipped.  Every
+    // iteration thus issues the same OX + OW loads, and since loads complete in issue order "at
+    // most (P-1)(OX + OW) loads outstanding" means all but the last P-1 iterations' have landed.
     // past the range the pointers stop: this workgroup's own last chunk again (a cache hit)
     const int glast = g1 > g0 ? g1 - 1 : g0;
     auto advance = [&]() {
