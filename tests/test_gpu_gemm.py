@@ -210,6 +210,44 @@ def test_prefill_mixed_launch(orc, sqp):
     assert ok, "worst err/tol %.3f, %d elements out of tolerance" % (worst, nbad)
 
 
+def _random_shapes(seed, count, m_lo, m_hi):
+    """Seeded random (M, K, N, group): K a multiple of the group, N a multiple of 8, sizes the
+    oracle finishes in a fraction of a second, spanning every kernel variant of the range."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for _ in range(count):
+        group = int(rng.choice([32, 64, 128, 128, 128, 256]))
+        K = group * int(rng.integers(1, max(2, 3072 // group)))
+        N = 8 * int(rng.integers(1, 160))
+        M = int(rng.integers(m_lo, m_hi + 1))
+        out.append((M, K, N, group))
+    return out
+
+
+@pytest.mark.parametrize("M,K,N,group", _random_shapes(101, 16, 1, 64))
+def test_decode_random_shapes(orc, sqp, M, K, N, group):
+    """Random small shapes through the streaming kernel with the library's own launch plan and
+    with a forced deep K split (where the chunk count allows it), against the oracle."""
+    print("case random decode", M, K, N, group, flush=True)
+    xs, p, sc, z = _layer(orc, M, K, N, group)
+    _check(orc, sqp, xs, p, sc, z, group)
+    L = sqp.lib()
+    L.sqp_debug_set_decode_plan(2, 5)
+    try:
+        _check(orc, sqp, xs, p, sc, z, group)
+    finally:
+        L.sqp_debug_set_decode_plan(0, 0)
+
+
+@pytest.mark.parametrize("M,K,N,group", _random_shapes(202, 8, 65, 700))
+def test_prefill_random_shapes(orc, sqp, M, K, N, group):
+    """Random shapes above 64 rows (tiled kernel: wide and narrow tiles, K parts; groups of 32
+    take the row-block fallback), against the oracle."""
+    print("case random prefill", M, K, N, group, flush=True)
+    xs, p, sc, z = _layer(orc, M, K, N, group)
+    _check(orc, sqp, xs, p, sc, z, group)
+
+
 def test_prefill_integer_exact(orc, sqp):
     """step = 1, Z = 0, small integer activations: exact integer product."""
     rng = np.random.Generator(np.random.PCG64(4))
