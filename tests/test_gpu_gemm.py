@@ -239,6 +239,21 @@ def test_decode_random_shapes(orc, sqp, M, K, N, group):
         L.sqp_debug_set_decode_plan(0, 0)
 
 
+@pytest.mark.parametrize("nw,split", [(1, 1), (1, 3), (8, 1), (8, 2)])
+@pytest.mark.parametrize("M,K,N,group", [(7, 1024, 1032, 128), (20, 512, 264, 64), (50, 768, 200, 32), (16, 1536, 520, 256)])
+def test_decode_other_strip_counts(orc, sqp, M, K, N, group, nw, split):
+    """The one- and eight-strip workgroups (which the launch plan does not pick by itself, but
+    which the library builds and the plan hook can select) through every row-tile variant."""
+    print("case strips", M, K, N, group, nw, split, flush=True)
+    xs, p, sc, z = _layer(orc, M, K, N, group)
+    L = sqp.lib()
+    L.sqp_debug_set_decode_plan(nw, split)
+    try:
+        _check(orc, sqp, xs, p, sc, z, group)
+    finally:
+        L.sqp_debug_set_decode_plan(0, 0)
+
+
 @pytest.mark.parametrize("M,K,N,group", _random_shapes(202, 8, 65, 700))
 def test_prefill_random_shapes(orc, sqp, M, K, N, group):
     """Random shapes above 64 rows (tiled kernel: wide and narrow tiles, K parts; groups of 32
