@@ -63,11 +63,15 @@ __device__ __forceinline__ void store_row4(h16 *y, int m, int N, int n, int epi,
 // Split-K tickets: one per 128-byte line (atomics on one line are served one after the other).
 constexpr int TICKET_STRIDE = 32;
 
-// MT: 16-row tiles of x (M <= 16*MT).  NW: waves (64-column strips) per workgroup.
+// MT: 16-row tiles of x (M <= 16*MT).  NW: 64-column strips per workgroup.
 // KSPG: k-steps (of 32) per chunk; a quantisation group is cpg chunks (cpg = 1 unless the
 // group is a multiple of 128 above 128).
-template <int MT, int NW, int KSPG>
-__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MT == 1 && NW >= 4 ? 3 : 1)))
+// KW: waves per strip.  With KW = 2 a strip's two waves share every chunk, each taking half of
+// its k-steps, and add their sums through LDS at the end: two waves per SIMD, whose
+// instructions the hardware interleaves, where a launch has only one workgroup per compute
+// unit and a single wave's dependent vector instructions would leave issue slots empty.
+template <int MT, int NW, int KSPG, int KW>
+__global__ void __launch_bounds__(NW * KW * 64) __attribute__((amdgpu_waves_per_eu(KW == 2 ? 2 : (MT == 1 && NW >= 4 ? 3 : 1))))
 w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, const uint32_t *__restrict__ packed,
                     const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y,
                     Workspace ws, int epi)
@@ -83,8 +87,11 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     constexpr int RPB = 16 / KSPG;         // rows per block
     constexpr int XBLOCKS = MT * KSPG;     // blocks per chunk
     constexpr int XSTAGE = XBLOCKS * 1024;
-    constexpr int OX = (XBLOCKS + NW - 1) / NW;  // direct loads per wave per chunk
-    constexpr int OW = KSPG + 2;                 // weight-side loads per wave per chunk
+    constexpr int WAVES = NW * KW;
+    constexpr int KS = KSPG / KW;                // k-steps of a chunk this wave takes
+    static_assert(KS * KW == KSPG, "k-steps divide among a strip's waves");
+    constexpr int OX = (XBLOCKS + WAVES - 1) / WAVES;  // direct loads per wave per chunk
+    constexpr int OW = KS + 2;                   // weight-side loads per wave per chunk
     // With four row tiles the per-chunk scaling of 64 accumulator registers costs more vector
     // work than multiplying the unpacked weights by the step (4 packed multiplies per word, as
     // in the tiled kernel), so that variant accumulates fp16(w_hat) products directly.
@@ -94,7 +101,8 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     __shared__ unsigned ticket_s;
 
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept scalar
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);    // wave-uniform, kept scalar
+    const int wave = wv % NW, kh = wv / NW;                             // strip, and which k-steps of a chunk
     const int lc = lane & 15, lk = lane >> 4;
     const int tile = blockIdx.x;
     const int n0 = tile * BN + wave * 64;
@@ -115,7 +123,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     const UnpackConsts uc = SQP_UNPACK_CONSTS;
 
     struct Stage {
-        u32x4 w[KSPG];
+        u32x4 w[KS];
         u32x2 sc;     // 4 fp16 steps
         uint32_t zr;  // 4 zero points, one byte each
     };
@@ -137,8 +145,8 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     int gi = g0, kin = g0 % cpg;                                 // chunk being issued, its position in its group
     auto issue_w = [&](Stage &s) {
 #pragma unroll
-        for (int ks = 0; ks < KSPG; ks++) {
-            const unsigned char *base = wq + ks * wstep1;        // wave-uniform
+        for (int ks = 0; ks < KS; ks++) {
+            const unsigned char *base = wq + (kh * KS + ks) * wstep1;  // wave-uniform
             asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
         }
         asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sq) : "memory");
@@ -149,7 +157,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     auto landed = [&](Stage &s, auto after) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(after)::value) : "memory");
 #pragma unroll
-        for (int ks = 0; ks < KSPG; ks++) asm volatile("" : "+v"(s.w[ks]));
+        for (int ks = 0; ks < KS; ks++) asm volatile("" : "+v"(s.w[ks]));
         asm volatile("" : "+v"(s.sc));
         asm volatile("" : "+v"(s.zr));
     };
@@ -163,7 +171,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     uint32_t xoff[OX];  // per-lane byte offset into x of each block this wave copies
 #pragma unroll
     for (int i = 0; i < OX; i++) {
-        const int b = (wave + i * NW) % XBLOCKS;
+        const int b = (wv + i * WAVES) % XBLOCKS;
         const int row = b * RPB + xrr;
         const int rowc = row < M ? row : M - 1;
         xoff[i] = (uint32_t)rowc * (uint32_t)K * 2u + (uint32_t)((xpp ^ (row % PP)) * 16);
@@ -171,7 +179,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     auto issue_x = [&](int slot) {
 #pragma unroll
         for (int i = 0; i < OX; i++) {
-            const int b = (wave + i * NW) % XBLOCKS;
+            const int b = (wv + i * WAVES) % XBLOCKS;
             const unsigned char *src = xq + xoff[i];
             unsigned char *dst = xring + slot * XSTAGE + b * 1024;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
@@ -211,7 +219,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         auto read_x = [&](u32x4 *dst, int ks) {
 #pragma unroll
             for (int mt = 0; mt < MT; mt++) {
-                const uint32_t a = xrd[mt] + (uint32_t)(slot * XSTAGE) + (uint32_t)(((ks * 4 + lk) ^ xsw) * 16);
+                const uint32_t a = xrd[mt] + (uint32_t)(slot * XSTAGE) + (uint32_t)((((kh * KS + ks) * 4 + lk) ^ xsw) * 16);
                 asm volatile("ds_read_b128 %0, %1" : "=&v"(dst[mt]) : "v"(a) : "memory");
             }
         };
@@ -222,12 +230,12 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         };
         if constexpr (MT == 1) {
             // one row tile: all k-steps' fragments in one batch (three waves per SIMD hide the rest)
-            u32x4 xa[KSPG];
+            u32x4 xa[KS];
 #pragma unroll
-            for (int ks = 0; ks < KSPG; ks++) read_x(&xa[ks], ks);
-            wait_x(xa, KSPG);
+            for (int ks = 0; ks < KS; ks++) read_x(&xa[ks], ks);
+            wait_x(xa, KS);
 #pragma unroll
-            for (int ks = 0; ks < KSPG; ks++) {
+            for (int ks = 0; ks < KS; ks++) {
                 const h16x8 a = permute_x(xa[ks]);
 #pragma unroll
                 for (int c = 0; c < 4; c++) {
@@ -244,9 +252,9 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
             read_x(xa[0], 0);
             wait_x(xa[0], MT);
 #pragma unroll
-            for (int ks = 0; ks < KSPG; ks++) {
+            for (int ks = 0; ks < KS; ks++) {
                 const int cur = ks & 1, nxt = cur ^ 1;
-                if (ks + 1 < KSPG) read_x(xa[nxt], ks + 1);
+                if (ks + 1 < KS) read_x(xa[nxt], ks + 1);
                 __builtin_amdgcn_sched_barrier(0);
                 h16x8 a[MT];
 #pragma unroll
@@ -271,7 +279,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // 1 MFMA
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (ks + 1 < KSPG) wait_x(xa[nxt], MT);
+                if (ks + 1 < KS) wait_x(xa[nxt], MT);
             }
         }
         if constexpr (!SCALED_B) {
@@ -343,7 +351,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 #pragma unroll
         for (int j = 0; j < D; j++) {
 #pragma unroll
-            for (int ks = 0; ks < KSPG; ks++) asm volatile("" ::"v"(st[j].w[ks]));
+            for (int ks = 0; ks < KS; ks++) asm volatile("" ::"v"(st[j].w[ks]));
             asm volatile("" ::"v"(st[j].sc));
             asm volatile("" ::"v"(st[j].zr));
         }
@@ -353,8 +361,25 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // column n0 + 4*(lane%16) + t.
     const int nout = n0 + 4 * lc;
     drain();
+    if constexpr (KW == 2) {
+        // A strip's two waves add their sums: the second wave's go through LDS (the activation
+        // ring is idle once every wave has passed the barrier), then only the first carries on.
+        static_assert(NW * REGS * 256 <= XD * XSTAGE, "the exchange fits the activation ring");
+        f32x4 *ex = reinterpret_cast<f32x4 *>(xring) + (size_t)wave * (REGS / 4) * 64 + lane;
+        __syncthreads();
+        if (kh == 1) {
+#pragma unroll
+            for (int q = 0; q < REGS / 4; q++) ex[q * 64] = acc[q / 4][q % 4];
+        }
+        __syncthreads();
+        if (kh == 0) {
+#pragma unroll
+            for (int q = 0; q < REGS / 4; q++) acc[q / 4][q % 4] += ex[q * 64];
+        }
+    }
+    const bool lead = kh == 0;  // the wave that stores the strip's results
     if (split == 1) {
-        if (nout < N) {
+        if (lead && nout < N) {
 #pragma unroll
             for (int mt = 0; mt < MT; mt++)
 #pragma unroll
@@ -378,7 +403,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         float *mine = ws.partial + (((size_t)tile * split + sidx) * NW + wave) * (64 * REGS) + lane * 4;
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
-            if (mt * 16 + 4 * lk < M) {  // lanes whose four rows are all past M have nothing to hand over
+            if (lead && mt * 16 + 4 * lk < M) {  // lanes whose four rows are all past M have nothing to hand over
 #pragma unroll
                 for (int t = 0; t < 4; t++)
                     // (the s_nop: a store of more than 8 bytes reads its data registers up to two wait
@@ -392,7 +417,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     if (threadIdx.x == 0) ticket_s = __hip_atomic_fetch_add(&ws.tickets[tile * TICKET_STRIDE], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket_s != (unsigned)(split - 1)) return;
-    {
+    if (lead) {
         const float *base = ws.partial + (((size_t)tile * split) * NW + wave) * (64 * REGS) + lane * 4;
         const size_t sstride = (size_t)NW * 64 * REGS;
         // Lanes whose four rows are all past M stored nothing and their sums are never written:
@@ -516,6 +541,9 @@ int sqp_partial_workspace(float **p, size_t *bytes, hipStream_t st)
 
 namespace {
 
+// Test/benchmark hook: 1 = never two waves per strip.
+int g_decode_kw = 0;
+
 template <int MT, int NW, int KSPG>
 int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t *packed, const h16 *scales,
            const uint8_t *zeros, h16 *y, int epi, hipStream_t st)
@@ -534,7 +562,15 @@ int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t
         int rc = get_workspace(&ws, st);
         if (rc) return rc;
     }
-    w4a16_decode_kernel<MT, NW, KSPG><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
+    // 16 rows, chunks of four k-steps, at most one workgroup per compute unit: two waves per
+    // strip (see the kernel's KW)
+    if constexpr (MT == 1 && KSPG == 4 && NW == 2) {
+        if (g_decode_kw != 1 && tiles * split <= 256) {
+            w4a16_decode_kernel<MT, NW, KSPG, 2><<<dim3(tiles, split), NW * 2 * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
+            return sqp_launch_status();
+        }
+    }
+    w4a16_decode_kernel<MT, NW, KSPG, 1><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
     return sqp_launch_status();
 }
 
@@ -547,9 +583,14 @@ struct Plan {
 // best with at most one workgroup per compute unit (256 in all; one more than that and a
 // second round of workgroups starts, which costs 20 % and more), each walking a long K
 // range; wider ones with two to three workgroups per unit.  More splits than that cost
-// more in fp32 partial tiles than the extra parallelism brings.  Where a narrow layer is
-// also short in K, so that 256 four-strip workgroups would get fewer than eight chunks
-// each, two strips per workgroup and half the split keep the pipelines longer.
+// more in fp32 partial tiles than the extra parallelism brings.
+// Two strips per workgroup with half the split: the same number of waves when each strip
+// has two (KW = 2: up to 16 rows, chunks of four k-steps), with half as many partial tiles to
+// hand over but the activations fetched by twice as many workgroups.  That wins on the
+// narrowest layers (up to 32 four-strip tiles) unless K is long (more than 24 chunks per
+// workgroup), where the streaming phase outweighs the hand-over.  Without the two-wave
+// variant, two strips only pay where 256 four-strip workgroups would get fewer than eight
+// chunks each.
 Plan make_plan(int M, int N, int K, int chunk)
 {
     const int chunks = K / chunk;
@@ -564,9 +605,11 @@ Plan make_plan(int M, int N, int K, int chunk)
     p.nw = 4;
     const int tiles4 = (N + 255) / 256;
     p.split = split_for(tiles4);
-    if (tiles4 <= 24 && chunks < 8 * (256 / tiles4)) {
+    const int split2 = split_for((N + 127) / 128);
+    const bool two_waves = M <= 16 && chunk == 128;  // the launch will give each strip two waves
+    if (two_waves ? (tiles4 <= 32 && chunks <= 24 * split2) : (tiles4 <= 24 && chunks < 8 * (256 / tiles4))) {
         p.nw = 2;
-        p.split = split_for((N + 127) / 128);
+        p.split = split2;
     }
     // More than 32 rows: the fp32 partial tiles are four times as large and the last arrival's
     // fetch of them is bound by its one compute unit, so the same waves are grouped into twice as
@@ -602,6 +645,7 @@ static int g_force_split = 0;
 static Plan g_force_plan = {0, 0};
 extern "C" void sqp_debug_set_decode_split(int split) { g_force_split = split; }
 extern "C" void sqp_debug_set_decode_plan(int nw, int split) { g_force_plan = Plan{nw, split}; }
+extern "C" void sqp_debug_set_decode_kw(int kw) { g_decode_kw = kw; }
 
 int sqp_gemm_generic(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
                      const uint8_t *zeros, h16 *y, hipStream_t stream)

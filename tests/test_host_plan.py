@@ -46,23 +46,25 @@ def test_decode_plan_invariants(L):
                     assert tiles * (split + 1) > 256
             elif split < max(1, chunks // 4):
                 assert abs(tiles * split - 704) <= tiles
-            if nw == 2:                                        # only narrow layers that are short in K
-                assert -(-N // 256) <= 24
+            if nw == 2:                                        # only narrow layers, and not with a long K range
+                assert -(-N // 256) <= (32 if group % 128 == 0 else 24)
+                if group % 128 == 0:
+                    assert chunks <= 24 * split
     assert _decode_plan(L, 16, 1024, 1024, 24)[2] == 0        # other group sizes: generic kernel
 
 
 def test_decode_plan_34b_values(L):
     """The plans the benchmark's launches run with (they are part of its configuration)."""
     got = {(K, N): _decode_plan(L, 16, N, K, 128)[:2] for (K, N) in wl.MODEL_SHAPES["34b"]}
-    assert got == {(8192, 10240): (4, 6), (8192, 8192): (4, 8), (8192, 44032): (4, 4), (22016, 8192): (4, 8)}
+    assert got == {(8192, 10240): (4, 6), (8192, 8192): (2, 4), (8192, 44032): (4, 4), (22016, 8192): (4, 8)}
 
 
 def test_decode_plan_many_rows(L):
     """More than 32 rows: two strips per workgroup, the split of the 16-row plan."""
     for (K, N) in wl.MODEL_SHAPES["34b"]:
-        nw16, split16, _ = _decode_plan(L, 16, N, K, 128)
-        assert _decode_plan(L, 32, N, K, 128)[:2] == (nw16, split16)
-        assert _decode_plan(L, 64, N, K, 128)[:2] == (2, split16)
+        nw32, split32, _ = _decode_plan(L, 32, N, K, 128)
+        assert nw32 == 4                                               # these layers are not tiny
+        assert _decode_plan(L, 64, N, K, 128)[:2] == (2, split32)
     assert _decode_plan(L, 64, 512, 256, 128)[:2] == (2, 1)            # short K: no split
     assert _decode_plan(L, 64, 65536, 256, 128)[:2] == (4, 1)
 
@@ -72,7 +74,8 @@ def test_decode_plan_small_model_values(L):
     assert _decode_plan(L, 16, 4096, 4096, 128)[:2] == (2, 8)      # narrow and short: two strips
     assert _decode_plan(L, 16, 5120, 5120, 128)[:2] == (2, 6)
     assert _decode_plan(L, 16, 4096, 11008, 128)[:2] == (2, 8)
-    assert _decode_plan(L, 16, 5120, 13824, 128)[:2] == (4, 12)    # long K: four strips, 240 workgroups
+    assert _decode_plan(L, 16, 5120, 13824, 128)[:2] == (2, 6)     # 40 two-strip tiles x 6 = 240 workgroups
+    assert _decode_plan(L, 32, 5120, 13824, 128)[:2] == (4, 12)    # no two-wave variant above 16 rows
     assert _decode_plan(L, 16, 22016, 4096, 128)[:2] == (4, 2)     # 86 tiles: 172 workgroups, not 258
 
 
