@@ -562,9 +562,9 @@ int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t
         int rc = get_workspace(&ws, st);
         if (rc) return rc;
     }
-    // 16 rows, chunks of four k-steps, at most one workgroup per compute unit: two waves per
-    // strip (see the kernel's KW)
-    if constexpr (MT == 1 && KSPG == 4 && NW == 2) {
+    // Up to 32 rows, chunks of four k-steps, two-strip workgroups, at most one workgroup per
+    // compute unit: two waves per strip (see the kernel's KW)
+    if constexpr (MT <= 2 && KSPG == 4 && NW == 2) {
         if (g_decode_kw != 1 && tiles * split <= 256) {
             w4a16_decode_kernel<MT, NW, KSPG, 2><<<dim3(tiles, split), NW * 2 * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
             return sqp_launch_status();
@@ -585,10 +585,11 @@ struct Plan {
 // range; wider ones with two to three workgroups per unit.  More splits than that cost
 // more in fp32 partial tiles than the extra parallelism brings.
 // Two strips per workgroup with half the split: the same number of waves when each strip
-// has two (KW = 2: up to 16 rows, chunks of four k-steps), with half as many partial tiles to
+// has two (KW = 2: up to 32 rows, chunks of four k-steps), with half as many partial tiles to
 // hand over but the activations fetched by twice as many workgroups.  That wins on the
 // narrowest layers (up to 32 four-strip tiles) unless K is long (more than 24 chunks per
-// workgroup), where the streaming phase outweighs the hand-over.  Without the two-wave
+// workgroup), where the streaming phase outweighs the hand-over; with 17 to 32 rows the
+// partial tiles are twice as large and it wins up to 40 tiles whatever K.  Without the two-wave
 // variant, two strips only pay where 256 four-strip workgroups would get fewer than eight
 // chunks each.
 Plan make_plan(int M, int N, int K, int chunk)
@@ -606,8 +607,12 @@ Plan make_plan(int M, int N, int K, int chunk)
     const int tiles4 = (N + 255) / 256;
     p.split = split_for(tiles4);
     const int split2 = split_for((N + 127) / 128);
-    const bool two_waves = M <= 16 && chunk == 128;  // the launch will give each strip two waves
-    if (two_waves ? (tiles4 <= 32 && chunks <= 24 * split2) : (tiles4 <= 24 && chunks < 8 * (256 / tiles4))) {
+    const bool two_waves = M <= 32 && chunk == 128;  // the launch will give each strip two waves
+    bool two_strips;
+    if (two_waves && M <= 16) two_strips = tiles4 <= 32 && chunks <= 24 * split2;
+    else if (two_waves) two_strips = tiles4 <= 40;  // 17..32 rows: partial tiles twice as large, so also with a long K
+    else two_strips = tiles4 <= 24 && chunks < 8 * (256 / tiles4);
+    if (two_strips) {
         p.nw = 2;
         p.split = split2;
     }

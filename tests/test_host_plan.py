@@ -62,9 +62,9 @@ def test_decode_plan_34b_values(L):
 def test_decode_plan_many_rows(L):
     """More than 32 rows: two strips per workgroup, the split of the 16-row plan."""
     for (K, N) in wl.MODEL_SHAPES["34b"]:
-        nw32, split32, _ = _decode_plan(L, 32, N, K, 128)
-        assert nw32 == 4                                               # these layers are not tiny
-        assert _decode_plan(L, 64, N, K, 128)[:2] == (2, split32)
+        tiles4, chunks = -(-N // 256), K // 128
+        four_strip_split = min(256 // tiles4 if tiles4 <= 128 else (704 + tiles4 // 2) // tiles4, max(1, chunks // 4))
+        assert _decode_plan(L, 48, N, K, 128)[:2] == (2, four_strip_split)
     assert _decode_plan(L, 64, 512, 256, 128)[:2] == (2, 1)            # short K: no split
     assert _decode_plan(L, 64, 65536, 256, 128)[:2] == (4, 1)
 
@@ -75,7 +75,10 @@ def test_decode_plan_small_model_values(L):
     assert _decode_plan(L, 16, 5120, 5120, 128)[:2] == (2, 6)
     assert _decode_plan(L, 16, 4096, 11008, 128)[:2] == (2, 8)
     assert _decode_plan(L, 16, 5120, 13824, 128)[:2] == (2, 6)     # 40 two-strip tiles x 6 = 240 workgroups
-    assert _decode_plan(L, 32, 5120, 13824, 128)[:2] == (4, 12)    # no two-wave variant above 16 rows
+    assert _decode_plan(L, 32, 5120, 13824, 128)[:2] == (2, 6)
+    assert _decode_plan(L, 32, 8192, 22016, 128)[:2] == (2, 4)     # 17..32 rows: also with a long K
+    assert _decode_plan(L, 16, 8192, 22016, 128)[:2] == (4, 8)
+    assert _decode_plan(L, 32, 12288, 4096, 128)[:2] == (4, 5)     # 48 tiles: four strips
     assert _decode_plan(L, 16, 22016, 4096, 128)[:2] == (4, 2)     # 86 tiles: 172 workgroups, not 258
 
 
