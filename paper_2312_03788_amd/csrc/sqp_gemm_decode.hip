@@ -195,7 +195,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     }
     const int xsw = lc % PP;  // the row's swizzle (16 % PP == 0, so mt does not matter)
 
-    auto compute = [&](const Stage &s, int slot, bool live) {
+    auto compute = [&](const Stage &s, int slot) {
         f32x4 accg[MT][4];
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
@@ -210,7 +210,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
             neg_lo[c] = neg_lo_of(z);
             const h16x2 sv = __builtin_bit_cast(h16x2, (uint32_t)s.sc[c >> 1]);
             const h16 d16 = (c & 1) ? sv.y : sv.x;
-            delta[c] = live ? (float)d16 : 0.f;
+            delta[c] = (float)d16;
             delta2[c] = h16x2{d16, d16};
         }
         // The A fragments come out of the LDS ring with reads written in assembly: the
@@ -229,7 +229,8 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
             for (int i = 0; i < n; i++) asm volatile("" : "+v"(dst[i]));  // no use ahead of the wait
         };
         if constexpr (MT == 1) {
-            // one row tile: all k-steps' fragments in one batch (three waves per SIMD hide the rest)
+            // one row tile: all of the wave's fragments of the chunk in one batch (other waves of
+            // the SIMD, where there are any, cover the wait)
             u32x4 xa[KS];
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) read_x(&xa[ks], ks);
@@ -336,7 +337,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
             issue_x(fill);
             issue_w(st[(d + P) % D]);
             advance();
-            if (gg < g1) compute(st[d], slot, true);  // padded iterations only keep the load counts in step
+            if (gg < g1) compute(st[d], slot);  // padded iterations only keep the load counts in step
             slot = slot + 1 == XD ? 0 : slot + 1;
         }
     }
