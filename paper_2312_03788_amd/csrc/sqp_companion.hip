@@ -7,6 +7,22 @@
 
 #pragma clang fp contract(off)
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Streaming accesses to the weight, every byte of which is touched once per call: the
+// non-temporal hint lets them pass through the caches (a plain read probe streams 12-15 %
+// faster with it on this chip; measured here: weight abs-max +7 %, weight scaling +4 %; no gain
+// for quantise + pack, and a loss for the much smaller activation tensor, which stay plain).
+__device__ __forceinline__ uint4 load_stream(const uint4 *p)
+{
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream(uint4 *p, const uint4 &v)
+{
+    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(p));
+}
+
 namespace {
 
 __device__ __forceinline__ float h2f_lo(uint32_t v) { return (float)__builtin_bit_cast(h16x2, v).x; }
@@ -72,7 +88,7 @@ __global__ void __launch_bounds__(256) absmax_w_factor_kernel(int N, float alpha
     const uint4 *row = w + (size_t)j * NO;
     float m = 0.0f;
     for (int o = threadIdx.x; o < NO; o += 256) {
-        uint4 v = row[o];
+        const uint4 v = load_stream(row + o);
         uint32_t q[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; i++) m = fmaxf(m, fmaxf(fabsf(h2f_lo(q[i])), fabsf(h2f_hi(q[i]))));
@@ -113,13 +129,13 @@ __global__ void __launch_bounds__(256) apply_w_kernel(long total_oct, int NO, co
     long i = (long)blockIdx.x * 256 + threadIdx.x;
     if (i >= total_oct) return;
     float sj = s[i / NO];
-    uint4 v = w[i];
+    uint4 v = load_stream(w + i);
     uint4 r;
     r.x = pack_h2(sj * h2f_lo(v.x), sj * h2f_hi(v.x));
     r.y = pack_h2(sj * h2f_lo(v.y), sj * h2f_hi(v.y));
     r.z = pack_h2(sj * h2f_lo(v.z), sj * h2f_hi(v.z));
     r.w = pack_h2(sj * h2f_lo(v.w), sj * h2f_hi(v.w));
-    out[i] = r;
+    store_stream(out + i, r);
 }
 
 // ------------------------------------------------------------------ Eq. 1

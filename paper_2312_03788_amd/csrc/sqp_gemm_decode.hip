@@ -131,7 +131,9 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // Weight-side addresses are a scalar base (advanced on the scalar unit) plus a per-lane
     // 32-bit offset that never changes, so the loads cost no vector arithmetic.  The loads are
     // written in assembly so that this kernel, not the compiler, decides when to wait for
-    // them: a stage must not be read before `landed` below.
+    // them: a stage must not be read before `landed` below.  They carry the non-temporal hint:
+    // every weight byte is read once per launch, and a plain streaming probe reads 12-15 % faster
+    // with it on this chip (the kernel gains about 2 %).
     const uint32_t voff_w = (uint32_t)(lk * N + ncol) * 4u;
     const int wrow_stride = N;
     const uint32_t voff_s = (uint32_t)ncol * 2u, voff_z = (uint32_t)ncol;
@@ -147,10 +149,10 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
             const unsigned char *base = wq + (kh * KS + ks) * wstep1;  // wave-uniform
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
+            asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
         }
-        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sq) : "memory");
-        asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zq) : "memory");
+        asm volatile("global_load_dwordx2 %0, %1, %2 nt" : "=v"(s.sc) : "v"(voff_s), "s"(sq) : "memory");
+        asm volatile("global_load_dword %0, %1, %2 nt" : "=v"(s.zr) : "v"(voff_z), "s"(zq) : "memory");
     };
     // wait until at most `after` loads are outstanding, then tie the stage's registers to the
     // wait so that no use of them is scheduled ahead of it
