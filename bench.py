@@ -28,7 +28,7 @@ MFMA_F16_PEAK_TFLOPS = 2516.6
 # HBM bytes per decode launch (averaged over the four shapes of the sweep) from the
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/w4a16_decode_34b_m16_hbm_traffic.md (34B shapes, M=16, default plan).
-TRAFFIC_BYTES_PER_LAUNCH = 105.5e6
+TRAFFIC_BYTES_PER_LAUNCH = 109.4e6
 
 
 def parse():
