@@ -9,10 +9,13 @@
  *   - Orientation follows Eq. 2: X is [M x K] (tokens x input channels), W is [K x N]
  *     (input channels x output channels), Y is [M x N]; all row-major, last index
  *     contiguous.
- *   - Every pointer is a DEVICE pointer owned by the caller and must be 16-byte aligned.
- *     fp16 data is IEEE binary16.  The library never frees or keeps caller memory.
+ *   - Every pointer is a DEVICE pointer owned by the caller and must be 16-byte aligned
+ *     (the fp64 outputs of the loss calls: 8-byte).  fp16 data is IEEE binary16.  The
+ *     library allocates no device memory, frees none, and keeps no caller memory except
+ *     the workspace pointer handed to sqp_set_workspace.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
- *     only enqueued; no call synchronises the device.
+ *     only enqueued; no call synchronises the device or allocates, so every call may be
+ *     recorded into a HIP graph.
  *   - Return value: SQP_OK (0), or a negative error code, in which case nothing was
  *     enqueued.  sqp_status_string() names a code.
  *   - Shape rules: M, N, K > 0; N % 8 == 0; K % 8 == 0; group % 8 == 0, group >= 8,
@@ -35,6 +38,7 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+#pragma GCC visibility push(default) /* the library is built with hidden visibility: these are its exports */
 
 #define SQP_OK 0
 #define SQP_ERR_NULL (-1)    /* a required pointer is NULL */
@@ -42,7 +46,7 @@ extern "C" {
 #define SQP_ERR_ALIGN (-3)   /* a pointer is not 16-byte aligned */
 #define SQP_ERR_ARG (-4)     /* alpha outside [0, 1] or not finite */
 #define SQP_ERR_LAUNCH (-5)  /* the HIP runtime reported an error at launch */
-#define SQP_ERR_WORKSPACE (-6) /* the library could not obtain its device workspace */
+#define SQP_ERR_WORKSPACE (-6) /* the workspace is too small for the launch plan of this shape */
 
 const char *sqp_status_string(int status);
 
@@ -113,13 +117,32 @@ int sqp_dequantize(int N, int K, int group, const uint32_t *packed, const void *
  * with fp32 accumulation and one rounding to fp16 at the end.  The result is
  * run-to-run deterministic.  x [M][K] fp16, y [M][N] fp16 out (must not alias x).
  * Rows M <= 64 take the weight-streaming (memory-bound) path, larger M the tiled
- * matrix-core path (with the inner dimension split across workgroups when the output has
- * too few tiles to occupy the chip).  Some shapes use a library-owned device workspace
- * (128 MB of fp32 partial sums per device) that is allocated on first use (so the first
- * such call may allocate; concurrent calls on different streams that both need it are
- * serialised by the caller). */
+ * matrix-core path.  When the output has too few tiles to occupy the chip, the launch plan
+ * splits the inner dimension across workgroups and passes fp32 partial sums through the
+ * workspace set with sqp_set_workspace:
+ *   - no workspace set: the plan without a split runs (same result within the tolerance of
+ *     Eq. 3's fp32 accumulation, slower on narrow layers);
+ *   - workspace smaller than sqp_w4a16_gemm_workspace_bytes() of the shape:
+ *     SQP_ERR_WORKSPACE, nothing enqueued.
+ * Calls that use the workspace must not overlap on the device (order them on one stream, or
+ * with events): they share its tickets and partial sums. */
 int sqp_w4a16_gemm(int M, int N, int K, int group, const void *x, const uint32_t *packed,
                    const void *scales, const uint8_t *zeros, void *y, void *stream);
+
+/* Bytes of workspace the launch plan of sqp_w4a16_gemm / sqp_w4a16_gemm_silu_mul uses for
+ * this shape on the current device: 0 if the plan does not split the inner dimension,
+ * otherwise 512 KB of tickets plus the fp32 partial sums.  Host arithmetic only. */
+size_t sqp_w4a16_gemm_workspace_bytes(int M, int N, int K, int group);
+
+/* Hands the library a caller-owned device buffer for the partial sums of Eq. 3's split
+ * launches on the CURRENT device (process-wide, one per device; the library keeps only the
+ * pointer).  The call enqueues one kernel on `stream` that zeroes the ticket area (the first
+ * 512 KB); GEMM calls must be ordered after it.  Every split launch leaves the tickets zero
+ * again, so the buffer is set once; after an aborted launch set it again.  The caller keeps
+ * the buffer alive until it sets another one or none: (NULL, 0) removes it.
+ * Errors: SQP_ERR_ALIGN; SQP_ERR_WORKSPACE if bytes <= 512 KB.  Not to be called while
+ * another thread is inside a GEMM call. */
+int sqp_set_workspace(void *dev_ptr, size_t bytes, void *stream);
 
 /* Quantisation loss of one layer, Eq. 4:  *loss = || x w - x_hat w_hat ||_F^2  with
  * w_hat the dequantised weights of (packed, scales, zeros) (Eq. 1) - the quantity the search
@@ -130,12 +153,31 @@ int sqp_w4a16_gemm(int M, int N, int K, int group, const void *x, const uint32_t
  *   x_hat [M][K] fp16  smoothed activations (Eq. 5)   packed/scales/zeros: quantised smoothed weight
  *   scratch  device, at least sqp_quant_loss_scratch_doubles(M, N) doubles, overwritten
  *   loss     device, one double (out)
- * All device pointers; nothing is allocated. */
+ * All device pointers (scratch and loss 8-byte aligned); nothing is allocated. */
 long sqp_quant_loss_scratch_doubles(int M, int N);
 int sqp_quant_loss(int M, int N, int K, int group, const void *x, const void *w, const void *x_hat,
                    const uint32_t *packed, const void *scales, const uint8_t *zeros, double *scratch,
                    double *loss, void *stream);
 
+/* Search of the smoothing strength for one layer (Sec 2.2: alpha is chosen on a grid to
+ * minimise the quantisation loss of Eq. 4; the paper's grid is 0, 0.05, ..., 1).  The
+ * per-channel maxima of Eq. 6 do not depend on alpha and are computed once; then for each
+ * alphas[i], in order:  s = Eq. 6,  x_hat = x_cal / s and w_s = s * w (Eq. 5),  w_s quantised
+ * (Eq. 1),  loss[i] = Eq. 4 on the calibration rows.  *best = index of the smallest loss (the
+ * lowest index on ties).  Every step is the kernel of the corresponding entry point above, so
+ * loss[i] equals what those calls would give, bit for bit.
+ *   alphas   HOST array of n_alpha values in [0, 1], 1 <= n_alpha <= 4096
+ *   x_cal [T][K] fp16, w [K][N] fp16                                    (in)
+ *   amax [2K] fp32, s [K] fp32, x_hat [T][K] fp16, w_s [K][N] fp16, packed / scales / zeros of
+ *   the layer's shape, scratch (sqp_quant_loss_scratch_doubles(T, N) doubles): device work
+ *   buffers, overwritten; on return they hold the last alpha's values
+ *   loss [n_alpha] fp64 device (out), best: one int, device (out)
+ * Nothing is allocated and nothing synchronises; errors as for the single calls. */
+int sqp_alpha_search(int T, int N, int K, int group, int n_alpha, const float *alphas, const void *x_cal,
+                     const void *w, float *amax, float *s, void *x_hat, void *w_s, uint32_t *packed,
+                     void *scales, uint8_t *zeros, double *scratch, double *loss, int *best, void *stream);
+
+#pragma GCC visibility pop
 #ifdef __cplusplus
 }
 #endif

@@ -14,7 +14,8 @@ _LIB_PATH = os.environ.get("SQP_LIBRARY", os.path.join(_HERE, "libsqp.so"))  # o
 
 EXPORTS = ["sqp_status_string", "sqp_smooth_scales", "sqp_smooth_apply_x", "sqp_smooth_apply_w",
            "sqp_quantize_pack", "sqp_dequantize", "sqp_w4a16_gemm", "sqp_quant_loss", "sqp_transpose_nk",
-           "sqp_w4a16_gemm_silu_mul", "sqp_rmsnorm", "sqp_scale_columns", "sqp_interleave_gate_up"]
+           "sqp_w4a16_gemm_silu_mul", "sqp_rmsnorm", "sqp_scale_columns", "sqp_interleave_gate_up",
+           "sqp_set_workspace", "sqp_alpha_search"]
 
 
 class SqpError(RuntimeError):
@@ -47,6 +48,10 @@ def lib():
         L.sqp_scale_columns.argtypes = [i, i, vp, vp, vp, vp]
         L.sqp_interleave_gate_up.argtypes = [i, i, vp, vp, vp, vp]
         L.sqp_quant_loss_scratch_doubles.argtypes = [i, i]
+        L.sqp_set_workspace.argtypes = [vp, ctypes.c_size_t, vp]
+        L.sqp_alpha_search.argtypes = [i, i, i, i, i, ctypes.POINTER(ctypes.c_float)] + [vp] * 13
+        L.sqp_w4a16_gemm_workspace_bytes.argtypes = [i, i, i, i]
+        L.sqp_w4a16_gemm_workspace_bytes.restype = ctypes.c_size_t
         for name in EXPORTS[1:]:
             getattr(L, name).restype = ctypes.c_int
         L.sqp_quant_loss_scratch_doubles.restype = ctypes.c_long
@@ -71,6 +76,45 @@ def _dev(t, dtype, name):
 
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+_workspaces = {}  # device index -> torch buffer handed to the library (kept alive here)
+
+
+def set_workspace(nbytes, device=None):
+    """Allocate a device buffer of `nbytes` with torch and hand it to the library as the
+    workspace for split launches of the GEMM on that device (sqp_set_workspace).  0 removes it.
+    Buffers set earlier stay referenced until the process ends: launches already enqueued
+    may still use them."""
+    dev = torch.device("cuda", torch.cuda.current_device()) if device is None else torch.device(device)
+    with torch.cuda.device(dev):
+        if nbytes <= 0:
+            _check(lib().sqp_set_workspace(None, 0, _stream()), "sqp_set_workspace")
+            _workspaces.setdefault(dev.index, []).append(None)
+            return None
+        buf = torch.empty(int(nbytes), dtype=torch.uint8, device=dev)
+        _check(lib().sqp_set_workspace(ctypes.c_void_p(buf.data_ptr()), int(nbytes), _stream()), "sqp_set_workspace")
+        _workspaces.setdefault(dev.index, []).append(buf)
+    return buf
+
+
+def workspace_bytes(M, N, K, group=128):
+    """Bytes of workspace the launch plan of the GEMM uses for this shape (0: none)."""
+    return int(lib().sqp_w4a16_gemm_workspace_bytes(M, N, K, group))
+
+
+def _ensure_workspace(M, N, K, group, device):
+    """Device-memory plumbing for the GEMM calls: make sure the workspace set on the tensor's
+    device covers this shape's plan (grown with some slack so that a sweep over shapes
+    settles after a few calls).  Callers that must not allocate (graph capture) call
+    set_workspace themselves beforehand."""
+    need = workspace_bytes(M, N, K, group)
+    if need == 0:
+        return
+    held = _workspaces.get(device.index)
+    have = held[-1].numel() if held and held[-1] is not None else 0
+    if need > have:
+        set_workspace(max(need, 2 * have, 16 << 20), device)
 
 
 def smooth_scales(x_cal, w, alpha, out=None):
@@ -139,6 +183,7 @@ def w4a16_gemm(x, packed, scales, zeros, group=128, out=None):
     if packed.shape[0] * 8 != K:
         raise SqpError("x and packed disagree on K")
     y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _ensure_workspace(M, N, K, group, x.device)
     _check(lib().sqp_w4a16_gemm(M, N, K, group, _dev(x, torch.float16, "x"), _dev(packed, torch.int32, "packed"),
                                 _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
                                 _dev(y, torch.float16, "y"), _stream()), "sqp_w4a16_gemm")
@@ -152,6 +197,7 @@ def w4a16_gemm_silu_mul(x, packed, scales, zeros, group=128, out=None):
     if packed.shape[0] * 8 != K:
         raise SqpError("x and packed disagree on K")
     y = out if out is not None else torch.empty((M, N // 2), dtype=torch.float16, device=x.device)
+    _ensure_workspace(M, N, K, group, x.device)
     _check(lib().sqp_w4a16_gemm_silu_mul(M, N, K, group, _dev(x, torch.float16, "x"), _dev(packed, torch.int32, "packed"),
                                          _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
                                          _dev(y, torch.float16, "y"), _stream()), "sqp_w4a16_gemm_silu_mul")
@@ -212,24 +258,35 @@ def quant_loss(x, w, x_hat, packed, scales, zeros, group=128, out=None):
 
 
 def alpha_search(x_cal, w, group=128, alphas=None):
-    """Single-layer search for the smoothing strength (Sec 2.2): for each alpha, Eq. 6 ->
-    Eq. 5 -> Eq. 1 -> Eq. 4 on the calibration activations, all in library kernels.
-    Returns (best alpha, list of (alpha, loss))."""
+    """Single-layer search for the smoothing strength (Sec 2.2) through sqp_alpha_search: the
+    per-channel maxima once, then Eq. 6 -> Eq. 5 -> Eq. 1 -> Eq. 4 per alpha and the argmin, all
+    in library kernels.  Returns (best alpha, list of (alpha, loss))."""
     if alphas is None:
         alphas = [0.05 * i for i in range(21)]
     T, K = x_cal.shape
     N = w.shape[1]
-    s = torch.empty(K, dtype=torch.float32, device=w.device)
+    if w.shape[0] != K or group <= 0 or K % group:
+        raise SqpError("x_cal, w and group disagree on K")
+    L = lib()
+    dev = w.device
+    n = len(alphas)
+    host_alphas = (ctypes.c_float * n)(*[float(a) for a in alphas])
+    amax = torch.empty(2 * K, dtype=torch.float32, device=dev)
+    s = torch.empty(K, dtype=torch.float32, device=dev)
     xh = torch.empty_like(x_cal)
     ws = torch.empty_like(w)
-    q = None
-    loss = torch.empty(len(alphas), dtype=torch.float64, device=w.device)
-    for i, a in enumerate(alphas):
-        smooth_scales(x_cal, w, float(a), out=s)
-        smooth_apply_x(x_cal, s, out=xh)
-        smooth_apply_w(w, s, out=ws)
-        q = quantize_pack(ws, group, out=q)
-        quant_loss(x_cal, w, xh, q[0], q[1], q[2], group, out=loss[i:i + 1])
+    packed = torch.empty((K // 8, N), dtype=torch.int32, device=dev)
+    scales = torch.empty((K // group, N), dtype=torch.float16, device=dev)
+    zeros = torch.empty((K // group, N), dtype=torch.uint8, device=dev)
+    scratch = torch.empty(int(L.sqp_quant_loss_scratch_doubles(T, N)), dtype=torch.float64, device=dev)
+    loss = torch.empty(n, dtype=torch.float64, device=dev)
+    best = torch.empty(1, dtype=torch.int32, device=dev)
+    _check(L.sqp_alpha_search(T, N, K, group, n, host_alphas, _dev(x_cal, torch.float16, "x_cal"), _dev(w, torch.float16, "w"),
+                              _dev(amax, torch.float32, "amax"), _dev(s, torch.float32, "s"), _dev(xh, torch.float16, "x_hat"),
+                              _dev(ws, torch.float16, "w_s"), _dev(packed, torch.int32, "packed"),
+                              _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
+                              _dev(scratch, torch.float64, "scratch"), _dev(loss, torch.float64, "loss"),
+                              _dev(best, torch.int32, "best"), _stream()), "sqp_alpha_search")
     vals = [float(v) for v in loss.cpu()]
-    best = min(range(len(alphas)), key=lambda i: vals[i])
-    return float(alphas[best]), list(zip([float(a) for a in alphas], vals))
+    b = int(best.cpu()[0])
+    return float(alphas[b]), list(zip([float(a) for a in alphas], vals))

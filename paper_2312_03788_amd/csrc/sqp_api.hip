@@ -79,8 +79,51 @@ static int g_decode_max_m = 64;
 // Test/benchmark hook: rows up to which the weight-streaming path is used.
 extern "C" void sqp_debug_set_decode_max_m(int m) { g_decode_max_m = m; }
 
-static int gemm_entry(int M, int N, int K, int group, const void *x, const uint32_t *packed, const void *scales,
-                      const uint8_t *zeros, void *y, int epi, void *stream)
+// ---------------------------------------------------------------- caller-owned workspace
+// One per device, set by sqp_set_workspace; the library only keeps the pointer.
+static SqpWorkspace g_caller_ws[64] = {};
+
+__global__ void __launch_bounds__(256) zero_tickets_kernel(unsigned *t, unsigned n)
+{
+    const unsigned i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) t[i] = 0u;
+}
+
+int sqp_zero_tickets(unsigned *tickets, hipStream_t stream)
+{
+    zero_tickets_kernel<<<(unsigned)(SQP_WS_TICKETS / 256), 256, 0, stream>>>(tickets, (unsigned)SQP_WS_TICKETS);
+    return sqp_launch_status();
+}
+
+SqpWorkspace sqp_caller_workspace()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SqpWorkspace{nullptr, nullptr, 0};
+    return g_caller_ws[dev];
+}
+
+extern "C" int sqp_set_workspace(void *dev_ptr, size_t bytes, void *stream)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SQP_ERR_WORKSPACE;
+    if (dev_ptr == nullptr || bytes == 0) {
+        g_caller_ws[dev] = SqpWorkspace{nullptr, nullptr, 0};
+        return SQP_OK;
+    }
+    if (sqp_misaligned(dev_ptr)) return SQP_ERR_ALIGN;
+    if (bytes <= SQP_WS_TICKET_BYTES) return SQP_ERR_WORKSPACE;
+    int rc = sqp_zero_tickets((unsigned *)dev_ptr, (hipStream_t)stream);
+    if (rc) return rc;
+    SqpWorkspace ws;
+    ws.tickets = (unsigned *)dev_ptr;
+    ws.partial = (float *)((unsigned char *)dev_ptr + SQP_WS_TICKET_BYTES);
+    ws.partial_bytes = (bytes - SQP_WS_TICKET_BYTES) & ~(size_t)15;
+    g_caller_ws[dev] = ws;
+    return SQP_OK;
+}
+
+static int check_gemm_args(int M, int N, int K, int group, const void *x, const uint32_t *packed, const void *scales,
+                           const uint8_t *zeros, const void *y)
 {
     if (!x || !packed || !scales || !zeros || !y) return SQP_ERR_NULL;
     if (M <= 0) return SQP_ERR_SHAPE;
@@ -89,18 +132,38 @@ static int gemm_entry(int M, int N, int K, int group, const void *x, const uint3
     if (sqp_too_big(M, K) || sqp_too_big(M, N)) return SQP_ERR_SHAPE;
     if (sqp_misaligned(x) || sqp_misaligned(packed) || sqp_misaligned(scales) || sqp_misaligned(zeros) || sqp_misaligned(y))
         return SQP_ERR_ALIGN;
+    return SQP_OK;
+}
+
+static bool streaming_path(int M) { return M <= g_decode_max_m && M <= 64; }
+
+extern "C" size_t sqp_w4a16_gemm_workspace_bytes(int M, int N, int K, int group)
+{
+    if (M <= 0 || sqp_check_quant_shape(N, K, group) != SQP_OK || sqp_too_big(M, K) || sqp_too_big(M, N)) return 0;
+    const size_t partial = streaming_path(M) ? sqp_gemm_decode_partial_bytes(M, N, K, group)
+                                             : sqp_gemm_prefill_partial_bytes(M, N, K, group);
+    return partial ? SQP_WS_TICKET_BYTES + partial : 0;
+}
+
+// Shared by every GEMM entry point: argument checks, then the weight-streaming path (small M)
+// or the tiled matrix-core path.
+int sqp_gemm_entry(int M, int N, int K, int group, const void *x, const uint32_t *packed, const void *scales,
+                   const uint8_t *zeros, void *y, int epi, const SqpWorkspace &ws, void *stream)
+{
+    int rc = check_gemm_args(M, N, K, group, x, packed, scales, zeros, y);
+    if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     const h16 *xp = (const h16 *)x;
     const h16 *sp = (const h16 *)scales;
     h16 *yp = (h16 *)y;
-    if (M <= g_decode_max_m && M <= 64) return sqp_gemm_decode(M, N, K, group, xp, packed, sp, zeros, yp, epi, st);
-    return sqp_gemm_prefill(M, N, K, group, xp, packed, sp, zeros, yp, epi, st);
+    if (streaming_path(M)) return sqp_gemm_decode(M, N, K, group, xp, packed, sp, zeros, yp, epi, ws, st);
+    return sqp_gemm_prefill(M, N, K, group, xp, packed, sp, zeros, yp, epi, ws, st);
 }
 
 extern "C" int sqp_w4a16_gemm(int M, int N, int K, int group, const void *x, const uint32_t *packed,
                               const void *scales, const uint8_t *zeros, void *y, void *stream)
 {
-    return gemm_entry(M, N, K, group, x, packed, scales, zeros, y, 0, stream);
+    return sqp_gemm_entry(M, N, K, group, x, packed, scales, zeros, y, 0, sqp_caller_workspace(), stream);
 }
 
 extern "C" int sqp_w4a16_gemm_silu_mul(int M, int N, int K, int group, const void *x, const uint32_t *packed,
@@ -109,5 +172,5 @@ extern "C" int sqp_w4a16_gemm_silu_mul(int M, int N, int K, int group, const voi
     if (N % 16) return SQP_ERR_SHAPE;          // the half-width output keeps 16-byte rows
     // the fused epilogue exists in the matrix-core kernels only
     if (!(group == 32 || group == 64 || group % 128 == 0)) return SQP_ERR_SHAPE;
-    return gemm_entry(M, N, K, group, x, packed, scales, zeros, y, 1, stream);
+    return sqp_gemm_entry(M, N, K, group, x, packed, scales, zeros, y, 1, sqp_caller_workspace(), stream);
 }

@@ -78,9 +78,19 @@ __global__ void __launch_bounds__(256) absmax_x_kernel(int T, int K, const uint4
     }
 }
 
-// One block per input channel j: aw = max_n |w[j][n]|, then Eq. 6 with ax read from
-// s[j] (left there by absmax_x_kernel) and s[j] overwritten with the factor.
-__global__ void __launch_bounds__(256) absmax_w_factor_kernel(int N, float alpha, const uint4 *w, float *s)
+__device__ __forceinline__ float smooth_factor_of(float ax, float aw, float alpha)
+{
+    ax = ax > 1e-5f ? ax : 1e-5f;
+    aw = aw > 1e-5f ? aw : 1e-5f;
+    const double a = (double)alpha;
+    return (float)(pow((double)ax, a) / pow((double)aw, 1.0 - a));
+}
+
+// One block per input channel j: aw = max_n |w[j][n]|.  FACTOR: then Eq. 6 with ax read from
+// s[j] (left there by absmax_x_kernel) and s[j] overwritten with the factor; otherwise aw is
+// stored to s[j].
+template <bool FACTOR>
+__global__ void __launch_bounds__(256) absmax_w_kernel(int N, float alpha, const uint4 *w, float *s)
 {
     __shared__ float red[4];
     const int j = blockIdx.x;
@@ -98,13 +108,16 @@ __global__ void __launch_bounds__(256) absmax_w_factor_kernel(int N, float alpha
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
     __syncthreads();
     if (threadIdx.x == 0) {
-        float aw = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-        float ax = s[j];
-        ax = ax > 1e-5f ? ax : 1e-5f;
-        aw = aw > 1e-5f ? aw : 1e-5f;
-        double a = (double)alpha;
-        s[j] = (float)(pow((double)ax, a) / pow((double)aw, 1.0 - a));
+        const float aw = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        s[j] = FACTOR ? smooth_factor_of(s[j], aw, alpha) : aw;
     }
+}
+
+// Eq. 6 from stored maxima: amax = [ax (K) | aw (K)].
+__global__ void __launch_bounds__(256) smooth_factor_kernel(int K, float alpha, const float *amax, float *s)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j < K) s[j] = smooth_factor_of(amax[j], amax[K + j], alpha);
 }
 
 // ------------------------------------------------------------------ Eq. 5
@@ -327,7 +340,25 @@ extern "C" int sqp_smooth_scales(int T, int K, int N, float alpha, const void *x
     int gy = (T + 63) / 64;
     if (gy > 64) gy = 64;
     absmax_x_kernel<<<dim3((K + 255) / 256, gy), 256, 0, st>>>(T, K, (const uint4 *)x_cal, (uint32_t *)s);
-    absmax_w_factor_kernel<<<K, 256, 0, st>>>(N, alpha, (const uint4 *)w, s);
+    absmax_w_kernel<true><<<K, 256, 0, st>>>(N, alpha, (const uint4 *)w, s);
+    return sqp_launch_status();
+}
+
+// The two halves of sqp_smooth_scales as separate steps (the per-channel maxima do not depend on
+// alpha, so a search over alpha computes them once): amax = [max_t|x_cal[t][j]| (K) | max_n|w[j][n]| (K)].
+int sqp_channel_absmax(int T, int K, int N, const void *x_cal, const void *w, float *amax, hipStream_t st)
+{
+    fill_zero_u32<<<(K + 255) / 256, 256, 0, st>>>((uint32_t *)amax, K);
+    int gy = (T + 63) / 64;
+    if (gy > 64) gy = 64;
+    absmax_x_kernel<<<dim3((K + 255) / 256, gy), 256, 0, st>>>(T, K, (const uint4 *)x_cal, (uint32_t *)amax);
+    absmax_w_kernel<false><<<K, 256, 0, st>>>(N, 0.0f, (const uint4 *)w, amax + K);
+    return sqp_launch_status();
+}
+
+int sqp_smooth_factor(int K, float alpha, const float *amax, float *s, hipStream_t st)
+{
+    smooth_factor_kernel<<<(K + 255) / 256, 256, 0, st>>>(K, alpha, amax, s);
     return sqp_launch_status();
 }
 

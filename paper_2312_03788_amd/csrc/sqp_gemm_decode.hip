@@ -496,74 +496,38 @@ w4a16_generic_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
     y[(size_t)m * N + n] = (h16)acc;
 }
 
-// ---------------------------------------------------------------- workspace
-
-constexpr size_t WS_PARTIAL_BYTES = (size_t)128 << 20;  // fp32 partial sums (decode split-K tiles, tiled-path K parts)
-constexpr int WS_TICKETS = 1 << 17;
-Workspace g_ws[16] = {};
-
-__global__ void zero_tickets_kernel(unsigned *t, int n)
-{
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) t[i] = 0u;
-}
-
-int get_workspace(Workspace *out, hipStream_t st)
-{
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return SQP_ERR_WORKSPACE;
-    if (!g_ws[dev].partial) {
-        void *p = nullptr, *t = nullptr;
-        if (hipMalloc(&p, WS_PARTIAL_BYTES) != hipSuccess) return SQP_ERR_WORKSPACE;
-        if (hipMalloc(&t, WS_TICKETS * sizeof(unsigned)) != hipSuccess) {
-            (void)hipFree(p);
-            return SQP_ERR_WORKSPACE;
-        }
-        zero_tickets_kernel<<<WS_TICKETS / 256, 256, 0, st>>>((unsigned *)t, WS_TICKETS);
-        g_ws[dev].partial = (float *)p;
-        g_ws[dev].tickets = (unsigned *)t;
-    }
-    *out = g_ws[dev];
-    return SQP_OK;
-}
-
-
-}  // namespace
-
-// The library's device workspace for fp32 partial sums, shared by both GEMM paths (calls on
-// one device are ordered by the caller's stream use, as the ABI header states).
-int sqp_partial_workspace(float **p, size_t *bytes, hipStream_t st)
-{
-    Workspace ws = {nullptr, nullptr};
-    int rc = get_workspace(&ws, st);
-    if (rc) return rc;
-    *p = ws.partial;
-    *bytes = WS_PARTIAL_BYTES;
-    return SQP_OK;
-}
-
-namespace {
+// ---------------------------------------------------------------- launch
 
 // Test/benchmark hook: 1 = never two waves per strip.
 int g_decode_kw = 0;
 
+// The split a launch really runs with (at most one part per chunk; none when the layer has
+// more tiles than the workspace has tickets: such a layer fills the chip anyway) and the
+// bytes of fp32 partial tiles it then leaves in the workspace.
+int effective_split(int mt, int nw, int kspg, int N, int K, int split, size_t *partial_bytes)
+{
+    const int tiles = (N + 64 * nw - 1) / (64 * nw);
+    const int chunks = K / (32 * kspg);
+    if (split > chunks) split = chunks;
+    if (split < 1) split = 1;
+    if ((size_t)tiles * TICKET_STRIDE > SQP_WS_TICKETS) split = 1;
+    *partial_bytes = split > 1 ? (size_t)tiles * split * nw * mt * 16 * 64 * sizeof(float) : 0;
+    return split;
+}
+
 template <int MT, int NW, int KSPG>
 int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t *packed, const h16 *scales,
-           const uint8_t *zeros, h16 *y, int epi, hipStream_t st)
+           const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &cws, hipStream_t st)
 {
     constexpr int BN = 64 * NW;
     const int tiles = (N + BN - 1) / BN;
-    const int chunks = K / (32 * KSPG);
-    if (split > chunks) split = chunks;
-    if (split < 1) split = 1;
+    size_t need = 0;
+    split = effective_split(MT, NW, KSPG, N, K, split, &need);
     Workspace ws = {nullptr, nullptr};
     if (split > 1) {
-        const size_t tile_bytes = (size_t)NW * MT * 16 * 64 * sizeof(float);
-        if (tiles * TICKET_STRIDE > WS_TICKETS || (size_t)tiles * split * tile_bytes > WS_PARTIAL_BYTES) split = 1;
-    }
-    if (split > 1) {
-        int rc = get_workspace(&ws, st);
-        if (rc) return rc;
+        if (!cws.partial || !cws.tickets || need > cws.partial_bytes) return SQP_ERR_WORKSPACE;
+        ws.partial = cws.partial;
+        ws.tickets = cws.tickets;
     }
     // Up to 32 rows, chunks of four k-steps, two-strip workgroups, at most one workgroup per
     // compute unit: two waves per strip (see the kernel's KW)
@@ -628,22 +592,22 @@ Plan make_plan(int M, int N, int K, int chunk)
 
 template <int MT, int KSPG>
 int dispatch_mt(const Plan &p, int M, int N, int K, int cpg, const h16 *x, const uint32_t *packed, const h16 *scales,
-                const uint8_t *zeros, h16 *y, int epi, hipStream_t st)
+                const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t st)
 {
-    if (p.nw == 1) return launch<MT, 1, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, st);
-    if (p.nw == 2) return launch<MT, 2, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, st);
+    if (p.nw == 1) return launch<MT, 1, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, ws, st);
+    if (p.nw == 2) return launch<MT, 2, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, ws, st);
     if constexpr (MT < 4)  // eight waves of the 64-row variant would not fit the register file
-        if (p.nw == 8) return launch<MT, 8, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, st);
-    return launch<MT, 4, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, st);
+        if (p.nw == 8) return launch<MT, 8, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, ws, st);
+    return launch<MT, 4, KSPG>(M, N, K, cpg, p.split, x, packed, scales, zeros, y, epi, ws, st);
 }
 
 template <int KSPG>
 int dispatch_kspg(const Plan &p, int M, int N, int K, int cpg, const h16 *x, const uint32_t *packed, const h16 *scales,
-                  const uint8_t *zeros, h16 *y, int epi, hipStream_t st)
+                  const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t st)
 {
-    if (M <= 16) return dispatch_mt<1, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, epi, st);
-    if (M <= 32) return dispatch_mt<2, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, epi, st);
-    return dispatch_mt<4, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, epi, st);
+    if (M <= 16) return dispatch_mt<1, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, epi, ws, st);
+    if (M <= 32) return dispatch_mt<2, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, epi, ws, st);
+    return dispatch_mt<4, KSPG>(p, M, N, K, cpg, x, packed, scales, zeros, y, epi, ws, st);
 }
 
 }  // namespace
@@ -675,16 +639,38 @@ extern "C" void sqp_debug_decode_plan(int M, int N, int K, int group, int *nw, i
     *kspg = group == 32 ? 1 : (group == 64 ? 2 : (group % 128 == 0 ? 4 : 0));
 }
 
-int sqp_gemm_decode(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
-                    const uint8_t *zeros, h16 *y, int epi, hipStream_t stream)
+// The plan a call runs with: the heuristic's, overridden by the test hooks, without a split
+// when there is no workspace to put partial sums in.
+static Plan plan_for(int M, int N, int K, int group, bool have_workspace)
 {
     const int chunk = group % 128 == 0 ? 128 : group;
     Plan p = make_plan(M, N, K, chunk);
     if (g_force_plan.nw > 0) p = g_force_plan;
     if (g_force_split > 0) p.split = g_force_split;
-    if (group == 32) return dispatch_kspg<1>(p, M, N, K, 1, x, packed, scales, zeros, y, epi, stream);
-    if (group == 64) return dispatch_kspg<2>(p, M, N, K, 1, x, packed, scales, zeros, y, epi, stream);
-    if (group % 128 == 0) return dispatch_kspg<4>(p, M, N, K, group / 128, x, packed, scales, zeros, y, epi, stream);
+    if (!have_workspace) p.split = 1;
+    return p;
+}
+
+size_t sqp_gemm_decode_partial_bytes(int M, int N, int K, int group)
+{
+    const int kspg = group == 32 ? 1 : (group == 64 ? 2 : (group % 128 == 0 ? 4 : 0));
+    if (kspg == 0) return 0;  // generic kernel
+    const Plan p = plan_for(M, N, K, group, true);
+    const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+    int nw = p.nw;
+    if (nw != 1 && nw != 2 && !(nw == 8 && mt < 4)) nw = 4;
+    size_t bytes = 0;
+    effective_split(mt, nw, kspg, N, K, p.split, &bytes);
+    return bytes;
+}
+
+int sqp_gemm_decode(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
+                    const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t stream)
+{
+    const Plan p = plan_for(M, N, K, group, ws.partial != nullptr);
+    if (group == 32) return dispatch_kspg<1>(p, M, N, K, 1, x, packed, scales, zeros, y, epi, ws, stream);
+    if (group == 64) return dispatch_kspg<2>(p, M, N, K, 1, x, packed, scales, zeros, y, epi, ws, stream);
+    if (group % 128 == 0) return dispatch_kspg<4>(p, M, N, K, group / 128, x, packed, scales, zeros, y, epi, ws, stream);
     if (epi != 0) return SQP_ERR_SHAPE;  // the fused activation needs a group size the matrix-core kernels cover
     return sqp_gemm_generic(M, N, K, group, x, packed, scales, zeros, y, stream);
 }

@@ -457,12 +457,12 @@ extern "C" void sqp_debug_set_prefill_ksplit(int k) { g_ksplit = k; }
 
 // The weight-streaming kernel, 64 rows at a time.
 static int decode_in_row_blocks(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
-                                const h16 *scales, const uint8_t *zeros, h16 *y, int epi, hipStream_t stream)
+                                const h16 *scales, const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t stream)
 {
     const size_t ystride = epi != 0 ? (size_t)(N >> 1) : (size_t)N;
     for (int mb = 0; mb < M; mb += 64) {
         int rows = M - mb < 64 ? M - mb : 64;
-        int rc = sqp_gemm_decode(rows, N, K, group, x + (size_t)mb * K, packed, scales, zeros, y + (size_t)mb * ystride, epi, stream);
+        int rc = sqp_gemm_decode(rows, N, K, group, x + (size_t)mb * K, packed, scales, zeros, y + (size_t)mb * ystride, epi, ws, stream);
         if (rc) return rc;
     }
     return SQP_OK;
@@ -475,7 +475,7 @@ struct TilePlan {
     int ksplit;
 };
 
-static TilePlan plan_tiles(int M, int N, int K, int cus, size_t workspace_bytes)
+static TilePlan plan_tiles(int M, int N, int K, int cus, bool have_workspace)
 {
     const int tn = (N + 255) / 256, tm = (M + BM - 1) / BM;
     const long tiles = (long)tn * tm;
@@ -483,7 +483,7 @@ static TilePlan plan_tiles(int M, int N, int K, int cus, size_t workspace_bytes)
     TilePlan p = {tiles, 0, 1};
     // (1) Too few tiles to occupy the chip even as half-width tiles: split K as well.  Half
     // tiles times K parts fill the compute units; every part leaves an fp32 [M][N] matrix in
-    // the library workspace and a second kernel adds the parts in order (deterministic).
+    // the workspace and a second kernel adds the parts in order (deterministic).
     int ksplit = 1;
     if (g_tile_mode == 0 && 4 * tiles <= cus) {
         ksplit = (int)(cus / (2 * tiles));
@@ -492,8 +492,7 @@ static TilePlan plan_tiles(int M, int N, int K, int cus, size_t workspace_bytes)
     }
     if (g_ksplit >= 0) ksplit = g_ksplit;
     if (ksplit > stages) ksplit = stages;
-    const size_t per_part = (size_t)M * N * sizeof(float);
-    if ((size_t)ksplit * per_part > workspace_bytes) ksplit = (int)(workspace_bytes / per_part);
+    if (!have_workspace) ksplit = 1;
     if (ksplit >= 2) {
         p.full = 0;
         p.half = 2 * tiles;
@@ -512,29 +511,31 @@ static TilePlan plan_tiles(int M, int N, int K, int cus, size_t workspace_bytes)
     return p;
 }
 
-constexpr size_t PARTIAL_WORKSPACE_BYTES = (size_t)128 << 20;  // what sqp_partial_workspace provides
-
 // Test hook: the plan for a shape on a chip of `cus` compute units (no launch, no GPU needed).
 extern "C" void sqp_debug_prefill_plan(int M, int N, int K, int cus, long *full, long *half, int *ksplit)
 {
-    const TilePlan p = plan_tiles(M, N, K, cus, PARTIAL_WORKSPACE_BYTES);
+    const TilePlan p = plan_tiles(M, N, K, cus, true);
     *full = p.full;
     *half = p.half;
     *ksplit = p.ksplit;
 }
 
+size_t sqp_gemm_prefill_partial_bytes(int M, int N, int K, int group)
+{
+    if (group % BK != 0) return sqp_gemm_decode_partial_bytes(M < 64 ? M : 64, N, K, group);  // row-block fallback
+    const TilePlan p = plan_tiles(M, N, K, compute_units(), true);
+    return p.ksplit >= 2 ? (size_t)p.ksplit * M * N * sizeof(float) : 0;
+}
+
 int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
-                     const h16 *scales, const uint8_t *zeros, h16 *y, int epi, hipStream_t stream)
+                     const h16 *scales, const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t stream)
 {
     if (group % BK == 0) {
         const int tn = (N + 255) / 256;
-        TilePlan p = plan_tiles(M, N, K, compute_units(), PARTIAL_WORKSPACE_BYTES);
+        TilePlan p = plan_tiles(M, N, K, compute_units(), ws.partial != nullptr);
         if (p.ksplit >= 2) {
-            float *part = nullptr;
-            size_t bytes = 0;
-            int rc = sqp_partial_workspace(&part, &bytes, stream);
-            if (rc) return rc;
-            if ((size_t)p.ksplit * M * N * sizeof(float) > bytes) return SQP_ERR_WORKSPACE;
+            if ((size_t)p.ksplit * M * N * sizeof(float) > ws.partial_bytes) return SQP_ERR_WORKSPACE;
+            float *part = ws.partial;
             w4a16_prefill_kernel<2, 4><<<dim3((unsigned)p.half, p.ksplit), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, part, epi);
             const long total8 = (long)M * N / 8;
             splitk_reduce_kernel<<<(unsigned)((total8 + 255) / 256), 256, 0, stream>>>(part, total8, (long)M * N, p.ksplit, y, epi);
@@ -547,5 +548,5 @@ int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_
         return sqp_launch_status();
     }
     // group sizes the tiled kernel does not cover
-    return decode_in_row_blocks(M, N, K, group, x, packed, scales, zeros, y, epi, stream);
+    return decode_in_row_blocks(M, N, K, group, x, packed, scales, zeros, y, epi, ws, stream);
 }

@@ -158,6 +158,16 @@ __global__ void __launch_bounds__(256) sum_partials_kernel(const double *__restr
     if (threadIdx.x == 0) *out = s[0];
 }
 
+// Index of the smallest of n values, the lowest index on ties (n is a grid of alphas: tiny).
+__global__ void argmin_kernel(const double *__restrict__ v, int n, int *__restrict__ best)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int b = 0;
+    for (int i = 1; i < n; i++)
+        if (v[i] < v[b]) b = i;
+    *best = b;
+}
+
 }  // namespace
 
 extern "C" long sqp_quant_loss_scratch_doubles(int M, int N)
@@ -178,11 +188,46 @@ extern "C" int sqp_quant_loss(int M, int N, int K, int group, const void *x, con
     if (sqp_misaligned(x) || sqp_misaligned(w) || sqp_misaligned(x_hat) || sqp_misaligned(packed) ||
         sqp_misaligned(scales) || sqp_misaligned(zeros))
         return SQP_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(scratch) & 7u) || (reinterpret_cast<uintptr_t>(loss) & 7u)) return SQP_ERR_ALIGN;
     const int gy = (M + LBM - 1) / LBM, gx = (N + LBN - 1) / LBN;
     if (gy > 65535) return SQP_ERR_SHAPE;
     hipStream_t st = (hipStream_t)stream;
     quant_loss_kernel<<<dim3(gx, gy), 256, 0, st>>>(M, N, K, group, (const h16 *)x, (const h16 *)w, (const h16 *)x_hat,
                                                    packed, (const h16 *)scales, zeros, scratch);
     sum_partials_kernel<<<1, 256, 0, st>>>(scratch, (long)gx * gy, loss);
+    return sqp_launch_status();
+}
+
+extern "C" int sqp_alpha_search(int T, int N, int K, int group, int n_alpha, const float *alphas, const void *x_cal,
+                                const void *w, float *amax, float *s, void *x_hat, void *w_s, uint32_t *packed,
+                                void *scales, uint8_t *zeros, double *scratch, double *loss, int *best, void *stream)
+{
+    if (!alphas || !x_cal || !w || !amax || !s || !x_hat || !w_s || !packed || !scales || !zeros || !scratch || !loss || !best)
+        return SQP_ERR_NULL;
+    if (T <= 0 || n_alpha <= 0 || n_alpha > 4096) return SQP_ERR_SHAPE;
+    int rc = sqp_check_quant_shape(N, K, group);
+    if (rc) return rc;
+    if (sqp_too_big(T, K) || sqp_too_big(T, N)) return SQP_ERR_SHAPE;
+    if ((T + LBM - 1) / LBM > 65535 || K / group > 65535) return SQP_ERR_SHAPE;
+    for (int i = 0; i < n_alpha; i++)
+        if (!(alphas[i] >= 0.0f && alphas[i] <= 1.0f)) return SQP_ERR_ARG;
+    if (sqp_misaligned(x_cal) || sqp_misaligned(w) || sqp_misaligned(amax) || sqp_misaligned(s) || sqp_misaligned(x_hat) ||
+        sqp_misaligned(w_s) || sqp_misaligned(packed) || sqp_misaligned(scales) || sqp_misaligned(zeros))
+        return SQP_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(scratch) & 7u) || (reinterpret_cast<uintptr_t>(loss) & 7u) ||
+        (reinterpret_cast<uintptr_t>(best) & 3u))
+        return SQP_ERR_ALIGN;
+    // every check any step below would make has passed: from here on only launch errors can occur
+    hipStream_t st = (hipStream_t)stream;
+    rc = sqp_channel_absmax(T, K, N, x_cal, w, amax, st);
+    for (int i = 0; i < n_alpha && rc == SQP_OK; i++) {
+        rc = sqp_smooth_factor(K, alphas[i], amax, s, st);
+        if (rc == SQP_OK) rc = sqp_smooth_apply_x(T, K, x_cal, s, x_hat, stream);
+        if (rc == SQP_OK) rc = sqp_smooth_apply_w(K, N, w, s, w_s, stream);
+        if (rc == SQP_OK) rc = sqp_quantize_pack(N, K, group, w_s, packed, scales, zeros, stream);
+        if (rc == SQP_OK) rc = sqp_quant_loss(T, N, K, group, x_cal, w, x_hat, packed, scales, zeros, scratch, loss + i, stream);
+    }
+    if (rc != SQP_OK) return rc;
+    argmin_kernel<<<1, 64, 0, st>>>(loss, n_alpha, best);
     return sqp_launch_status();
 }

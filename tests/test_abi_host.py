@@ -15,13 +15,40 @@ def L():
     return sqp.lib()
 
 
+def _declared(header):
+    hdr = open(os.path.join(ROOT, "include", header)).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)  # prose in comments is not a declaration
+    return set(re.findall(r"\b(sqp_[a-z0-9_]+)\s*\(", hdr))
+
+
 def test_exports_match_header(L):
-    hdr = open(os.path.join(ROOT, "include", "sqp.h")).read()
-    declared = set(re.findall(r"\b(sqp_[a-z0-9_]+)\s*\(", hdr))
+    """The functions the shared library exports are exactly those the two headers declare:
+    the product ABI (sqp.h) and the test/benchmark hooks (sqp_test_hooks.h)."""
+    import subprocess
+    api, hooks = _declared("sqp.h"), _declared("sqp_test_hooks.h")
     assert {"sqp_smooth_scales", "sqp_smooth_apply_x", "sqp_smooth_apply_w", "sqp_quantize_pack",
-            "sqp_dequantize", "sqp_w4a16_gemm", "sqp_status_string"} <= declared
-    for name in declared:
+            "sqp_dequantize", "sqp_w4a16_gemm", "sqp_status_string", "sqp_set_workspace",
+            "sqp_w4a16_gemm_workspace_bytes"} <= api
+    assert all(n.startswith("sqp_debug_") for n in hooks) and not any(n.startswith("sqp_debug_") for n in api)
+    for name in api | hooks:
         assert hasattr(L, name), name
+    out = subprocess.run(["nm", "-D", "--defined-only", L._name], check=True, stdout=subprocess.PIPE, text=True).stdout
+    exported = {ln.split()[2] for ln in out.splitlines() if len(ln.split()) == 3 and ln.split()[1] == "T"}
+    exported = {n for n in exported if not n.startswith("_")}  # _init / _fini
+    assert exported == api | hooks, (sorted(exported - api - hooks), sorted((api | hooks) - exported))
+
+
+def test_workspace_bytes(L):
+    """The size query: zero for shapes whose plan does not split K and for invalid shapes,
+    tickets + partial tiles otherwise (34B 8192 -> 8192 at M = 16: two-strip tiles, 4 parts)."""
+    q = L.sqp_w4a16_gemm_workspace_bytes
+    q.restype = ctypes.c_size_t
+    assert q(16, 8192, 8192, 128) == (512 << 10) + 64 * 4 * (2 * 16 * 64 * 4)
+    assert q(16, 1 << 20, 256, 128) == 0        # wide and short: no split
+    assert q(16, 8192, 8190, 128) == 0          # invalid shape
+    assert q(0, 8192, 8192, 128) == 0
+    assert q(4096, 44032, 8192, 128) == 0       # many tiles: no K parts
+    assert q(256, 8192, 8192, 128) == (512 << 10) + 4 * 256 * 8192 * 4   # tiled path, 4 K parts
 
 
 def test_status_strings(L):
