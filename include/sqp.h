@@ -159,6 +159,23 @@ int sqp_quant_loss(int M, int N, int K, int group, const void *x, const void *w,
                    const uint32_t *packed, const void *scales, const uint8_t *zeros, double *scratch,
                    double *loss, void *stream);
 
+/* sqp_w4a16_gemm for callers that cannot allocate device memory and own no workspace: code
+ * recorded under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, kernels, launch plans and results as sqp_w4a16_gemm with a sufficient
+ * workspace set (bit-identical), but the tickets and partial sums of split launches live in a
+ * static device array of the library: 512 KB + SQP_STATIC_PARTIAL_BYTES per device, held
+ * until the process ends.  The call allocates nothing and ignores sqp_set_workspace.
+ *   - A shape whose plan needs more partial sums than SQP_STATIC_PARTIAL_BYTES
+ *     (sqp_w4a16_gemm_workspace_bytes(shape) - 512 KB) is refused with SQP_ERR_WORKSPACE,
+ *     nothing enqueued.  The library's own plans stay below the limit for every shape.
+ *   - The first call on a device looks the array up and enqueues one extra kernel that zeroes
+ *     its tickets; make that call outside a graph capture.
+ *   - All calls on one device share the array: calls that overlap on the device race (order
+ *     them on one stream or with events), as do overlaps with nothing else in this library. */
+#define SQP_STATIC_PARTIAL_BYTES ((size_t)48 << 20)
+int sqp_w4a16_gemm_static(int M, int N, int K, int group, const void *x, const uint32_t *packed,
+                          const void *scales, const uint8_t *zeros, void *y, void *stream);
+
 /* Search of the smoothing strength for one layer (Sec 2.2: alpha is chosen on a grid to
  * minimise the quantisation loss of Eq. 4; the paper's grid is 0, 0.05, ..., 1).  The
  * per-channel maxima of Eq. 6 do not depend on alpha and are computed once; then for each

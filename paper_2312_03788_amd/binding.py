@@ -15,7 +15,7 @@ _LIB_PATH = os.environ.get("SQP_LIBRARY", os.path.join(_HERE, "libsqp.so"))  # o
 EXPORTS = ["sqp_status_string", "sqp_smooth_scales", "sqp_smooth_apply_x", "sqp_smooth_apply_w",
            "sqp_quantize_pack", "sqp_dequantize", "sqp_w4a16_gemm", "sqp_quant_loss", "sqp_transpose_nk",
            "sqp_w4a16_gemm_silu_mul", "sqp_rmsnorm", "sqp_scale_columns", "sqp_interleave_gate_up",
-           "sqp_set_workspace", "sqp_alpha_search"]
+           "sqp_set_workspace", "sqp_alpha_search", "sqp_w4a16_gemm_static"]
 
 
 class SqpError(RuntimeError):
@@ -44,6 +44,7 @@ def lib():
         L.sqp_quant_loss.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.sqp_transpose_nk.argtypes = [i, i, vp, vp, vp]
         L.sqp_w4a16_gemm_silu_mul.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp]
+        L.sqp_w4a16_gemm_static.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp]
         L.sqp_rmsnorm.argtypes = [i, i, vp, vp, f, vp, vp]
         L.sqp_scale_columns.argtypes = [i, i, vp, vp, vp, vp]
         L.sqp_interleave_gate_up.argtypes = [i, i, vp, vp, vp, vp]
@@ -187,6 +188,21 @@ def w4a16_gemm(x, packed, scales, zeros, group=128, out=None):
     _check(lib().sqp_w4a16_gemm(M, N, K, group, _dev(x, torch.float16, "x"), _dev(packed, torch.int32, "packed"),
                                 _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
                                 _dev(y, torch.float16, "y"), _stream()), "sqp_w4a16_gemm")
+    return y
+
+
+def w4a16_gemm_static(x, packed, scales, zeros, group=128, out=None):
+    """Eq. 3 through the entry point that allocates nothing and needs no workspace (partial
+    sums in the library's static device array); `out` should be passed by callers that must
+    not allocate."""
+    M, K = x.shape
+    N = packed.shape[1]
+    if packed.shape[0] * 8 != K:
+        raise SqpError("x and packed disagree on K")
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _check(lib().sqp_w4a16_gemm_static(M, N, K, group, _dev(x, torch.float16, "x"), _dev(packed, torch.int32, "packed"),
+                                       _dev(scales, torch.float16, "scales"), _dev(zeros, torch.uint8, "zeros"),
+                                       _dev(y, torch.float16, "y"), _stream()), "sqp_w4a16_gemm_static")
     return y
 
 

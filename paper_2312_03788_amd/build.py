@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsqp.so")
 
-SOURCES = ["sqp_api.hip", "sqp_companion.hip", "sqp_gemm_decode.hip", "sqp_gemm_prefill.hip", "sqp_loss.hip", "sqp_mlp.hip"]
+SOURCES = ["sqp_api.hip", "sqp_companion.hip", "sqp_gemm_decode.hip", "sqp_gemm_prefill.hip", "sqp_loss.hip", "sqp_mlp.hip", "sqp_static.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-I" + os.path.join(ROOT, "include"),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
