@@ -270,6 +270,123 @@ __global__ void __launch_bounds__(256) quantize_pack_reg_kernel(int N, const uin
     }
 }
 
+// Groups of 128 rows, the configuration of every benchmark layer: a block of 256 threads
+// quantises 128 rows x 256 columns.  Thread (part = tid / 32, oct = tid % 32) holds rows
+// 16 part .. 16 part + 15 of columns 8 oct .. 8 oct + 7 in registers (16 loads of 16 bytes; a
+// wave's load covers two rows x 512 contiguous bytes).  Column minima and maxima (exact packed
+// fp16 min / max) meet in LDS; the step, the zero point and the reciprocal step of column
+// 8 oct + part are then computed by thread (part, oct) alone (three IEEE divisions per column,
+// not per thread and column) and handed to the other parts through LDS.  Coding pass, per
+// weight: t = fma(w, 1 / Delta, Z) -- within 1.9e-6 of (correctly rounded w / Delta) + Z
+// wherever the code is not clamped, see NEAR_TIE -- then round, clamp to [0, 15] as a float,
+// and the eight codes of a word are assembled by a fused multiply-add chain (sum c_i 16^i per
+// half word is exact in fp32).  A word containing a value within NEAR_TIE of a rounding tie is
+// redone with the division of the definition (wave-uniform branch, about 0.4 % of the words).
+__global__ void __launch_bounds__(256) quantize_pack_g128_kernel(int N, const uint4 *__restrict__ w, uint32_t *__restrict__ packed,
+                                                                 uint16_t *__restrict__ scales, uint8_t *__restrict__ zeros)
+{
+    __shared__ uint4 red[8][2][32];     // [part][min | max][oct]: 8 KB
+    __shared__ float par_d[256], par_inv[256], par_z[256];  // per column of the block
+    const int oct = threadIdx.x & 31, part = threadIdx.x >> 5;
+    const int NO = N >> 3;
+    const int o = blockIdx.x * 32 + oct;
+    const bool in = o < NO;
+    const int t = blockIdx.y;
+    const uint4 *wp = w + ((size_t)t * 128 + (size_t)part * 16) * NO + (in ? o : 0);
+    uint4 v[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) v[i] = load_stream(wp + (size_t)i * NO);
+    h16x2 mn[4], mx[4];
+    {
+        const uint32_t q[4] = {v[0].x, v[0].y, v[0].z, v[0].w};
+#pragma unroll
+        for (int c = 0; c < 4; c++) mn[c] = mx[c] = __builtin_bit_cast(h16x2, q[c]);
+    }
+#pragma unroll
+    for (int i = 1; i < 16; i++) {
+        const uint32_t q[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            const h16x2 e = __builtin_bit_cast(h16x2, q[c]);
+            mn[c] = __builtin_elementwise_min(mn[c], e);
+            mx[c] = __builtin_elementwise_max(mx[c], e);
+        }
+    }
+    auto as_u4 = [](const h16x2 (&a)[4]) {
+        return make_uint4(__builtin_bit_cast(uint32_t, a[0]), __builtin_bit_cast(uint32_t, a[1]),
+                          __builtin_bit_cast(uint32_t, a[2]), __builtin_bit_cast(uint32_t, a[3]));
+    };
+    red[part][0][oct] = as_u4(mn);
+    red[part][1][oct] = as_u4(mx);
+    __syncthreads();
+    {
+        // thread (part, oct): column 8 oct + part, i.e. half (part & 1) of dword (part >> 1) of the octet
+        const uint32_t *rmn = reinterpret_cast<const uint32_t *>(&red[0][0][oct]) + (part >> 1);
+        const uint32_t *rmx = reinterpret_cast<const uint32_t *>(&red[0][1][oct]) + (part >> 1);
+        constexpr int PSTRIDE = 2 * 32 * 4;  // dwords between parts
+        float lo = 0.f, hi = 0.f;
+#pragma unroll
+        for (int pp = 0; pp < 8; pp++) {
+            const h16x2 a = __builtin_bit_cast(h16x2, rmn[pp * PSTRIDE]), b = __builtin_bit_cast(h16x2, rmx[pp * PSTRIDE]);
+            const float fa = (part & 1) ? (float)a.y : (float)a.x, fb = (part & 1) ? (float)b.y : (float)b.x;
+            lo = pp == 0 ? fa : fminf(lo, fa);
+            hi = pp == 0 ? fb : fmaxf(hi, fb);
+        }
+        const GroupParams gp = group_params(lo, hi);
+        const int col = oct * 8 + part;
+        par_d[col] = gp.d;
+        par_inv[col] = 1.0f / gp.d;
+        par_z[col] = (float)gp.z;
+        const int n = blockIdx.x * 256 + col;
+        if (n < N) {
+            scales[(size_t)t * N + n] = gp.d16;
+            zeros[(size_t)t * N + n] = (uint8_t)gp.z;
+        }
+    }
+    __syncthreads();
+    if (!in) return;
+    uint32_t *pp0 = packed + ((size_t)t * 16 + (size_t)part * 2) * N + (size_t)o * 8;
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+        uint32_t word[8];
+#pragma unroll
+        for (int c = 0; c < 8; c++) {
+            const float inv = par_inv[oct * 8 + c], zf = par_z[oct * 8 + c];
+            float code[8], worst = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const uint4 &row = v[8 * j + i];
+                const uint32_t dw = (c >> 1) == 0 ? row.x : ((c >> 1) == 1 ? row.y : ((c >> 1) == 2 ? row.z : row.w));
+                const float x = (c & 1) ? h2f_hi(dw) : h2f_lo(dw);
+                const float tq = fmaf(x, inv, zf);
+                const float r = rintf(tq);
+                worst = fmaxf(worst, fabsf(tq - r));
+                code[i] = fminf(fmaxf(r, 0.0f), 15.0f);
+            }
+            const float lo4 = fmaf(fmaf(fmaf(code[3], 16.0f, code[2]), 16.0f, code[1]), 16.0f, code[0]);
+            const float hi4 = fmaf(fmaf(fmaf(code[7], 16.0f, code[6]), 16.0f, code[5]), 16.0f, code[4]);
+            word[c] = (uint32_t)lo4 | ((uint32_t)hi4 << 16);
+            if (__builtin_amdgcn_ballot_w64(worst >= 0.5f - NEAR_TIE) != 0ull) {
+                GroupParams gp;
+                gp.d = par_d[oct * 8 + c];
+                gp.z = (int)zf;
+                gp.d16 = 0;
+                uint32_t wd = 0;
+#pragma unroll
+                for (int i = 0; i < 8; i++) {
+                    const uint4 &row = v[8 * j + i];
+                    const uint32_t dw = (c >> 1) == 0 ? row.x : ((c >> 1) == 1 ? row.y : ((c >> 1) == 2 ? row.z : row.w));
+                    wd |= code_of((c & 1) ? h2f_hi(dw) : h2f_lo(dw), gp) << (4 * i);
+                }
+                word[c] = wd;
+            }
+        }
+        uint4 *dst = reinterpret_cast<uint4 *>(pp0 + (size_t)j * N);
+        dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
+        dst[1] = make_uint4(word[4], word[5], word[6], word[7]);
+    }
+}
+
 // Any group size (multiple of 8): the group is read twice.
 __global__ void __launch_bounds__(256) quantize_pack_any_kernel(int N, int G, const uint32_t *w, uint2 *packed, uint32_t *scales, uint16_t *zeros)
 {
@@ -439,7 +556,9 @@ extern "C" int sqp_quantize_pack(int N, int K, int group, const void *w, uint32_
     switch (group) {
         case 32: quantize_pack_reg_kernel<32, 1><<<grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
         case 64: quantize_pack_reg_kernel<64, SQP_QP_SPLIT64><<<SQP_QP_SPLIT64 == 2 ? grid2 : grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
-        case 128: quantize_pack_reg_kernel<128, SQP_QP_SPLIT128><<<SQP_QP_SPLIT128 == 2 ? grid2 : grid, 256, 0, st>>>(N, wp, pp, sp, zp); break;
+        case 128:
+            quantize_pack_g128_kernel<<<dim3((N + 255) / 256, K / 128), 256, 0, st>>>(N, (const uint4 *)w, packed, (uint16_t *)scales, zeros);
+            break;
         default: quantize_pack_any_kernel<<<grid, 256, 0, st>>>(N, group, wp, pp, sp, zp); break;
     }
     return sqp_launch_status();

@@ -145,14 +145,60 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     const unsigned char *zq = zeros + (long)(g0 / cpg) * N;
     const unsigned char *xq = reinterpret_cast<const unsigned char *>(x) + (long)g0 * (64 * KSPG);
     int gi = g0, kin = g0 % cpg;                                 // chunk being issued, its position in its group
-    auto issue_w = [&](Stage &s) {
-#pragma unroll
-        for (int ks = 0; ks < KS; ks++) {
-            const unsigned char *base = wq + (kh * KS + ks) * wstep1;  // wave-uniform
-            asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
+    // `live` (wave-uniform) is false for the look-ahead loads past the end of the workgroup's range:
+    // those are issued with an empty execution mask, so they fetch nothing (with the streaming
+    // hint their lines would not be cache hits) and write no register, but still take their
+    // place in the in-order load queue, which keeps the wait counts below the same for every
+    // iteration.  Mask change, loads and mask restore are one asm statement, so the compiler can
+    // place nothing of its own under the changed mask.
+    auto issue_w = [&](Stage &s, bool live) {
+        const unsigned char *b0 = wq + (kh * KS) * wstep1;  // wave-uniform
+        const uint32_t m = __builtin_amdgcn_readfirstlane(live ? 0xffffffffu : 0u);  // both halves of the mask
+        uint64_t saved;
+        if constexpr (KS == 4) {
+            const unsigned char *b1 = b0 + wstep1, *b2 = b0 + 2 * wstep1, *b3 = b0 + 3 * wstep1;
+            asm volatile("s_mov_b64 %[sv], exec\n\t"
+                         "s_and_b32 exec_lo, exec_lo, %[m]\n\t"
+                         "s_and_b32 exec_hi, exec_hi, %[m]\n\t"
+                         "global_load_dwordx4 %[w0], %[vw], %[b0] nt\n\t"
+                         "global_load_dwordx4 %[w1], %[vw], %[b1] nt\n\t"
+                         "global_load_dwordx4 %[w2], %[vw], %[b2] nt\n\t"
+                         "global_load_dwordx4 %[w3], %[vw], %[b3] nt\n\t"
+                         "global_load_dwordx2 %[sc], %[vs], %[sq] nt\n\t"
+                         "global_load_dword %[zr], %[vz], %[zq] nt\n\t"
+                         "s_mov_b64 exec, %[sv]"
+                         : [w0] "=&v"(s.w[0]), [w1] "=&v"(s.w[1]), [w2] "=&v"(s.w[2]), [w3] "=&v"(s.w[3]), [sc] "=&v"(s.sc),
+                           [zr] "=&v"(s.zr), [sv] "=&s"(saved)
+                         : [m] "s"(m), [vw] "v"(voff_w), [vs] "v"(voff_s), [vz] "v"(voff_z), [b0] "s"(b0), [b1] "s"(b1),
+                           [b2] "s"(b2), [b3] "s"(b3), [sq] "s"(sq), [zq] "s"(zq)
+                         : "memory", "scc");  // s_and_b32 writes SCC
+        } else if constexpr (KS == 2) {
+            const unsigned char *b1 = b0 + wstep1;
+            asm volatile("s_mov_b64 %[sv], exec\n\t"
+                         "s_and_b32 exec_lo, exec_lo, %[m]\n\t"
+                         "s_and_b32 exec_hi, exec_hi, %[m]\n\t"
+                         "global_load_dwordx4 %[w0], %[vw], %[b0] nt\n\t"
+                         "global_load_dwordx4 %[w1], %[vw], %[b1] nt\n\t"
+                         "global_load_dwordx2 %[sc], %[vs], %[sq] nt\n\t"
+                         "global_load_dword %[zr], %[vz], %[zq] nt\n\t"
+                         "s_mov_b64 exec, %[sv]"
+                         : [w0] "=&v"(s.w[0]), [w1] "=&v"(s.w[1]), [sc] "=&v"(s.sc), [zr] "=&v"(s.zr), [sv] "=&s"(saved)
+                         : [m] "s"(m), [vw] "v"(voff_w), [vs] "v"(voff_s), [vz] "v"(voff_z), [b0] "s"(b0), [b1] "s"(b1),
+                           [sq] "s"(sq), [zq] "s"(zq)
+                         : "memory", "scc");  // s_and_b32 writes SCC
+        } else {
+            static_assert(KS == 1, "k-steps per wave and chunk");
+            asm volatile("s_mov_b64 %[sv], exec\n\t"
+                         "s_and_b32 exec_lo, exec_lo, %[m]\n\t"
+                         "s_and_b32 exec_hi, exec_hi, %[m]\n\t"
+                         "global_load_dwordx4 %[w0], %[vw], %[b0] nt\n\t"
+                         "global_load_dwordx2 %[sc], %[vs], %[sq] nt\n\t"
+                         "global_load_dword %[zr], %[vz], %[zq] nt\n\t"
+                         "s_mov_b64 exec, %[sv]"
+                         : [w0] "=&v"(s.w[0]), [sc] "=&v"(s.sc), [zr] "=&v"(s.zr), [sv] "=&s"(saved)
+                         : [m] "s"(m), [vw] "v"(voff_w), [vs] "v"(voff_s), [vz] "v"(voff_z), [b0] "s"(b0), [sq] "s"(sq), [zq] "s"(zq)
+                         : "memory", "scc");  // s_and_b32 writes SCC
         }
-        asm volatile("global_load_dwordx2 %0, %1, %2 nt" : "=v"(s.sc) : "v"(voff_s), "s"(sq) : "memory");
-        asm volatile("global_load_dword %0, %1, %2 nt" : "=v"(s.zr) : "v"(voff_z), "s"(zq) : "memory");
     };
     // wait until at most `after` loads are outstanding, then tie the stage's registers to the
     // wait so that no use of them is scheduled ahead of it
@@ -302,11 +348,11 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // (stage index static: the loop is unrolled by D), consume chunk g.  The pipeline is primed
     // by issuing chunks g0 .. g0+P-1.
     // The loading side of the loop body is free of branches: the chunk count is rounded up to a
-    // multiple of D and loads past the range are clamped to the range's last chunk (cache hits,
-    // no extra HBM traffic); only the arithmetic of such padded iterations is skipped.  Every
-    // iteration thus issues the same OX + OW loads, and since loads complete in issue order "at
-    // most (P-1)(OX + OW) loads outstanding" means all but the last P-1 iterations' have landed.
-    // past the range the pointers stop: this workgroup's own last chunk again (a cache hit)
+    // multiple of D; loads past the range point at the range's last chunk (the activations: cache
+    // hits) or are issued with an empty execution mask (the weight side); the arithmetic of such
+    // padded iterations is skipped.  Every iteration thus issues the same OX + OW loads, and
+    // since loads complete in issue order "at most (P-1)(OX + OW) loads outstanding" means all
+    // but the last P-1 iterations' have landed.  Past the range the pointers stop.
     const int glast = g1 > g0 ? g1 - 1 : g0;
     auto advance = [&]() {
         const bool more = gi < glast;
@@ -323,7 +369,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 #pragma unroll
     for (int j = 0; j < P; j++) {
         issue_x(j);
-        issue_w(st[j]);
+        issue_w(st[j], g0 + j < g1);
         advance();
     }
     int slot = 0;  // ring slot of chunk g
@@ -337,17 +383,17 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
             asm volatile("s_barrier" ::: "memory");
             const int fill = slot >= 1 ? slot - 1 : XD - 1;  // (slot + P) % XD
             issue_x(fill);
-            issue_w(st[(d + P) % D]);
+            issue_w(st[(d + P) % D], gg + P < g1);
             advance();
             if (gg < g1) compute(st[d], slot);  // padded iterations only keep the load counts in step
             slot = slot + 1 == XD ? 0 : slot + 1;
         }
     }
-    // The clamped look-ahead loads are still in flight here.  Their destination registers are
-    // dead by now as far as the compiler can tell, but the hardware still writes them when the
-    // data arrives: `drain` waits for everything outstanding and its empty uses keep every stage
-    // allocated until then, so that nothing else is placed in those registers while a load is in
-    // flight.  It runs after the epilogue's stores have been issued (they only read the
+    // Look-ahead loads may still be in flight here (a range shorter than the pipeline issues
+    // real loads it never consumes).  Their destination registers are dead by now as far as the
+    // compiler can tell, but the hardware still writes them when the data arrives: `drain` waits
+    // for everything outstanding and its empty uses keep every stage allocated until then, so
+    // that nothing else is placed in those registers while a load is in flight.  It runs after the epilogue's stores have been issued (they only read the
     // accumulators), so that one wait covers both.
     auto drain = [&]() {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -401,7 +447,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // is the ticket taken.  Layout: [tile][split][wave][Q][lane][4] floats (each instruction
     // moves 1 KB contiguous per wave).
     constexpr int Q = REGS / 4;                         // 16-byte pieces per lane
-    constexpr int SB = 32 / Q;                          // partials fetched per round trip (128 registers)
+    constexpr int SB = MT == 1 ? 6 : 32 / Q;            // partials fetched per round trip (what fits the register budget without spilling)
     {
         float *mine = ws.partial + (((size_t)tile * split + sidx) * NW + wave) * (64 * REGS) + lane * 4;
 #pragma unroll

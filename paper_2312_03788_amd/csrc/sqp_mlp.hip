@@ -54,6 +54,50 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(int H8, float inv_h, float
     }
 }
 
+// The same with the row held in registers between the two passes (rows of up to 2048 NI halves):
+// the input is read once.  The sum of squares is formed in the same order as above, so both
+// kernels give the same bits.
+template <int NI>
+__global__ void __launch_bounds__(256) rmsnorm_reg_kernel(int H8, float inv_h, float eps, const uint4 *__restrict__ x,
+                                                          const uint4 *__restrict__ gamma, uint4 *__restrict__ y)
+{
+    __shared__ float red[4];
+    const uint4 *xr = x + (size_t)blockIdx.x * H8;
+    uint4 v[NI];
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < NI; j++) {
+        const int i = threadIdx.x + 256 * j;
+        v[j] = make_uint4(0, 0, 0, 0);
+        if (i < H8) {
+            v[j] = xr[i];
+            const float a0 = lo_of(v[j].x), a1 = hi_of(v[j].x), a2 = lo_of(v[j].y), a3 = hi_of(v[j].y);
+            const float a4 = lo_of(v[j].z), a5 = hi_of(v[j].z), a6 = lo_of(v[j].w), a7 = hi_of(v[j].w);
+            ss += ((a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3)) + ((a4 * a4 + a5 * a5) + (a6 * a6 + a7 * a7));
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float total = (red[0] + red[1]) + (red[2] + red[3]);
+    const float r = 1.0f / sqrtf(total * inv_h + eps);
+    uint4 *yr = y + (size_t)blockIdx.x * H8;
+#pragma unroll
+    for (int j = 0; j < NI; j++) {
+        const int i = threadIdx.x + 256 * j;
+        if (i < H8) {
+            const uint4 g = gamma[i];
+            uint4 o;
+            o.x = pack2(lo_of(v[j].x) * r * lo_of(g.x), hi_of(v[j].x) * r * hi_of(g.x));
+            o.y = pack2(lo_of(v[j].y) * r * lo_of(g.y), hi_of(v[j].y) * r * hi_of(g.y));
+            o.z = pack2(lo_of(v[j].z) * r * lo_of(g.z), hi_of(v[j].z) * r * hi_of(g.z));
+            o.w = pack2(lo_of(v[j].w) * r * lo_of(g.w), hi_of(v[j].w) * r * hi_of(g.w));
+            yr[i] = o;
+        }
+    }
+}
+
 __global__ void __launch_bounds__(256) scale_columns_kernel(long total_oct, int NO, const uint4 *__restrict__ w,
                                                             const float4 *__restrict__ s, uint4 *__restrict__ out)
 {
@@ -96,7 +140,17 @@ extern "C" int sqp_rmsnorm(int M, int H, const void *x, const void *gamma, float
     if (M <= 0 || H <= 0 || (H % 8) || sqp_too_big(M, H)) return SQP_ERR_SHAPE;
     if (!(eps >= 0.0f) || !(eps < 1.0f)) return SQP_ERR_ARG;
     if (sqp_misaligned(x) || sqp_misaligned(gamma) || sqp_misaligned(y)) return SQP_ERR_ALIGN;
-    rmsnorm_kernel<<<(unsigned)M, 256, 0, (hipStream_t)stream>>>(H / 8, 1.0f / (float)H, eps, (const uint4 *)x, (const uint4 *)gamma, (uint4 *)y);
+    const int H8 = H / 8;
+    const float inv_h = 1.0f / (float)H;
+    hipStream_t st = (hipStream_t)stream;
+    const uint4 *xp = (const uint4 *)x, *gp = (const uint4 *)gamma;
+    uint4 *yp = (uint4 *)y;
+    if (H8 <= 256) rmsnorm_reg_kernel<1><<<(unsigned)M, 256, 0, st>>>(H8, inv_h, eps, xp, gp, yp);
+    else if (H8 <= 512) rmsnorm_reg_kernel<2><<<(unsigned)M, 256, 0, st>>>(H8, inv_h, eps, xp, gp, yp);
+    else if (H8 <= 1024) rmsnorm_reg_kernel<4><<<(unsigned)M, 256, 0, st>>>(H8, inv_h, eps, xp, gp, yp);
+    else if (H8 <= 2048) rmsnorm_reg_kernel<8><<<(unsigned)M, 256, 0, st>>>(H8, inv_h, eps, xp, gp, yp);
+    else if (H8 <= 4096) rmsnorm_reg_kernel<16><<<(unsigned)M, 256, 0, st>>>(H8, inv_h, eps, xp, gp, yp);
+    else rmsnorm_kernel<<<(unsigned)M, 256, 0, st>>>(H8, inv_h, eps, xp, gp, yp);
     return sqp_launch_status();
 }
 

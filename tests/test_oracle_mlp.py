@@ -60,3 +60,21 @@ def test_folding_is_an_identity_in_exact_arithmetic(orc):
     ref = orc.mlp_block_ref(x, gamma, 1e-5, wg, wu, wd)
     folded = orc.mlp_block_ref(x, gamma / s1, 1e-5, s1[:, None] * wg, s1[:, None] * wu / s2[None, :], s2[:, None] * wd)
     assert np.allclose(folded, ref, rtol=1e-11, atol=1e-11)
+
+
+def test_mlp_block_hand_value(orc):
+    """A block small enough to work by hand (Fig. 5's structure: norm -> gate, up -> SiLU(gate) * up
+    -> down).  x = (3, 4), eps = 3.5: mean square 12.5, divisor 4, so with gamma = (4, 2) the
+    normalised row is n = (3, 2).  gate = n . (1, -1) = 1 and n . (0, 0) = 0; up = n . (1, 1) = 5 and
+    n . (2, -1) = 4.  Hidden row: (SiLU(1) * 5, SiLU(0) * 4) = (5 / (1 + e^-1), 0).  down column
+    (2, 7) gives 10 / (1 + e^-1); a second down column (0, 1) gives 0."""
+    x = [[3.0, 4.0]]
+    w_gate = [[1.0, 0.0], [-1.0, 0.0]]
+    w_up = [[1.0, 2.0], [1.0, -1.0]]
+    w_down = [[2.0, 0.0], [7.0, 1.0]]
+    y = orc.mlp_block_ref(x, [4.0, 2.0], 3.5, w_gate, w_up, w_down)
+    want = 10.0 / (1.0 + math.exp(-1.0))
+    assert y.shape == (1, 2)
+    assert abs(y[0, 0] - want) <= 1e-14 * want and y[0, 1] == 0.0
+    # a transposed weight or gate and up swapped would give other values
+    assert abs(orc.mlp_block_ref(x, [4.0, 2.0], 3.5, w_up, w_gate, w_down)[0, 0] - want) > 0.1
