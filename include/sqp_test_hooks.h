@@ -24,10 +24,11 @@ void sqp_debug_set_decode_kw(int kw);              /* 1 = never two waves per st
 void sqp_debug_decode_plan(int M, int N, int K, int group, int *nw, int *split, int *kspg);
 
 /* Tiled matrix-core path (M > 64). */
-void sqp_debug_set_prefill_tiles(int mode);        /* 0 = automatic, 1 = 256-column tiles only, 2 = 128-column only */
+void sqp_debug_set_prefill_tiles(int mode);        /* 0 = automatic, 1 = full tiles only, 2 = half-width tiles only */
+void sqp_debug_set_prefill_shape(int shape);       /* 0 = automatic, 1 = 128 x 512 full tiles, 2 = 256 x 256 */
 void sqp_debug_set_prefill_ksplit(int k);          /* -1 = automatic, 0 or 1 = never, k >= 2 = k parts */
-/* The tile plan for a shape on a chip of `cus` compute units: 256-column tiles of the first
- * launch, 128-column tiles of the second, K parts.  Host arithmetic only. */
+/* The tile plan for a shape on a chip of `cus` compute units: full tiles of the first launch,
+ * half-width tiles of the second, K parts.  Host arithmetic only. */
 void sqp_debug_prefill_plan(int M, int N, int K, int cus, long *full, long *half, int *ksplit);
 
 /* Calibration kernels for the benchmark: a plain device copy of `bytes` (a multiple of 16)

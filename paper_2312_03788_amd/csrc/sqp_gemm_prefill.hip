@@ -31,37 +31,47 @@
 
 namespace {
 
-constexpr int BM = 256, BK = 64;
+constexpr int BK = 64;
 
-// NT: 32-column MFMA tiles per wave; W: waves, arranged 2 (rows) x W/2 (columns).
-// <4, 4>: the workgroup covers 256 columns (wave tile 128 x 128).  <2, 4>: 128 columns (wave
-// tile 128 x 64), used for the tiles left over after the last full round of 256-column tiles
-// so that the tail of a launch costs half a round.  <2, 8>: 256 columns with two waves per SIMD.
-// Workgroup b of the launch handles tile tile0 + b / (256 / columns) of the tn x tm grid of
-// 256 x 256 tiles (column index fastest), column half b % 2 of it when it covers 128.
-template <int NT, int W>
-__global__ void __launch_bounds__(W * 64)
+// NT: 32-column MFMA tiles per wave (wave tile 128 rows x 32 NT columns); WM: waves along the
+// rows, the other 4 / WM along the columns.
+//   <4, 1>: 128 x 512 tile, the four waves side by side on the same 128 rows.  Every packed word
+//           is then loaded and unpacked by exactly one wave, and a workgroup stages half as
+//           many activation bytes per matrix instruction as with the square tile.
+//   <4, 2>: 256 x 256 tile, waves 2 x 2 (the two waves of a column pair unpack the same words).
+//   <2, *>: the same with half the columns (128 x 256 / 256 x 128), used for the tiles left over
+//           after the last full round so that the tail of a launch costs half a round, and for
+//           the K-split launches.
+// Workgroup b of the launch handles tile tile0 + b / (full columns / columns) of the tn x tm grid
+// of full tiles (column index fastest), column half b % 2 of it when it covers half.
+template <int NT, int WM>
+__global__ void __launch_bounds__(256)
 w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h16 *__restrict__ x,
                      const uint32_t *__restrict__ packed, const h16 *__restrict__ scales,
                      const uint8_t *__restrict__ zeros, h16 *__restrict__ y, float *__restrict__ part, int epi)
 {
+    constexpr int W = 4;                   // waves: one per SIMD
+    constexpr int WNW = W / WM;            // waves along the columns
+    constexpr int BM = 128 * WM;           // rows per workgroup
+    constexpr int FULLN = WNW * 128;       // columns of a full tile of this arrangement
     constexpr int WN = 32 * NT;            // columns per wave
     typedef uint32_t wvec __attribute__((ext_vector_type(NT)));
     typedef std::conditional_t<NT == 4, u32x2, uint32_t> scvec;
     constexpr int D = 3;                   // register stages of packed weights (two in flight)
     constexpr int XD = 4;                  // LDS slots of activations
-    constexpr int XSTAGE = BM * BK * 2;   // 32 KB: 32 blocks of 8 rows x 128 bytes
-    constexpr int OX = 32 / W;             // direct loads per wave per stage (32 blocks of 1 KB)
-    constexpr int WGN = (W / 2) * WN;      // columns per workgroup: 256 or 128
+    constexpr int XSTAGE = BM * BK * 2;   // 16 or 32 KB: blocks of 8 rows x 128 bytes
+    constexpr int OX = (BM / 8) / W;       // direct loads per wave per stage (one per 1 KB block)
+    constexpr int WGN = WNW * WN;          // columns per workgroup: a full tile's or half of them
+    static_assert(OX % 4 == 0, "the loads of a stage are spread evenly over its four k-steps");
     constexpr int OW = 4 + 2;
     __shared__ __attribute__((aligned(1024))) unsigned char xring[XD * XSTAGE];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave / (W / 2), wn = wave % (W / 2);
+    const int wm = wave / WNW, wn = wave % WNW;
     const int l32 = lane & 31, kb = lane >> 5;
-    const int tile = tile0 + (int)blockIdx.x / (256 / WGN);
-    const int nbase = (tile % tn) * 256 + (WGN == 256 ? 0 : ((int)blockIdx.x & 1) * 128);
+    const int tile = tile0 + (int)blockIdx.x / (FULLN / WGN);
+    const int nbase = (tile % tn) * FULLN + (WGN == FULLN ? 0 : ((int)blockIdx.x & 1) * WGN);
     const int m0 = (tile / tn) * BM;
     const int n0 = nbase + wn * WN;
     // K split across gridDim.y workgroups (part != nullptr): this one takes stages
@@ -349,8 +359,8 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     const int e_l32 = tid & 31, e_kb = (tid >> 5) & 1, e_wave = tid >> 6;
-    const int nout = nbase + (e_wave % (W / 2)) * WN + NT * e_l32;
-    const int mrow0 = m0 + (e_wave / (W / 2)) * 128 + 4 * e_kb;
+    const int nout = nbase + (e_wave % WNW) * WN + NT * e_l32;
+    const int mrow0 = m0 + (e_wave / WNW) * 128 + 4 * e_kb;
     if (part != nullptr) {
         if (nout < N) {
             float *pcol = part + (size_t)blockIdx.y * M * N + nout;
@@ -444,16 +454,13 @@ int compute_units()
 
 }  // namespace
 
-#ifndef SQP_PF_MAIN_W
-#define SQP_PF_MAIN_W 4
-#endif
-constexpr int MAIN_W = SQP_PF_MAIN_W, MAIN_NT = MAIN_W == 8 ? 2 : 4;
-
-// Test/benchmark hooks.  Tiles: 0 = automatic tile choice, 1 = 256-column tiles only, 2 =
-// 128-column tiles only.  K split: -1 = automatic, 0 or 1 = never, k >= 2 = k parts.
-static int g_tile_mode = 0, g_ksplit = -1;
+// Test/benchmark hooks.  Tiles: 0 = automatic tile choice, 1 = full tiles only, 2 = half tiles
+// only.  K split: -1 = automatic, 0 or 1 = never, k >= 2 = k parts.  Shape: 0 = automatic,
+// 1 = 128 x 512 full tiles (waves 1 x 4), 2 = 256 x 256 (waves 2 x 2).
+static int g_tile_mode = 0, g_ksplit = -1, g_tile_shape = 0;
 extern "C" void sqp_debug_set_prefill_tiles(int mode) { g_tile_mode = mode; }
 extern "C" void sqp_debug_set_prefill_ksplit(int k) { g_ksplit = k; }
+extern "C" void sqp_debug_set_prefill_shape(int shape) { g_tile_shape = shape; }
 
 // The weight-streaming kernel, 64 rows at a time.
 static int decode_in_row_blocks(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
@@ -468,19 +475,22 @@ static int decode_in_row_blocks(int M, int N, int K, int group, const h16 *x, co
     return SQP_OK;
 }
 
-// Launch plan of the tiled path: `full` 256-column tiles in a first launch, then `half`
-// 128-column tiles (starting at tile `full`), the latter times `ksplit` K parts.
+// Launch plan of the tiled path: `full` full tiles (128 x 512 with wm == 1, 256 x 256 with
+// wm == 2) in a first launch, then `half` half-width tiles (starting at full tile `full`), the
+// latter times `ksplit` K parts.
 struct TilePlan {
     long full, half;
-    int ksplit;
+    int ksplit, wm;
 };
 
 static TilePlan plan_tiles(int M, int N, int K, int cus, bool have_workspace)
 {
-    const int tn = (N + 255) / 256, tm = (M + BM - 1) / BM;
+    const int wm = g_tile_shape == 2 ? 2 : 1;
+    const int bm = 128 * wm, fulln = (4 / wm) * 128;
+    const int tn = (N + fulln - 1) / fulln, tm = (M + bm - 1) / bm;
     const long tiles = (long)tn * tm;
     const int stages = K / BK;
-    TilePlan p = {tiles, 0, 1};
+    TilePlan p = {tiles, 0, 1, wm};
     // (1) Too few tiles to occupy the chip even as half-width tiles: split K as well.  Half
     // tiles times K parts fill the compute units; every part leaves an fp32 [M][N] matrix in
     // the workspace and a second kernel adds the parts in order (deterministic).
@@ -527,25 +537,34 @@ size_t sqp_gemm_prefill_partial_bytes(int M, int N, int K, int group)
     return p.ksplit >= 2 ? (size_t)p.ksplit * M * N * sizeof(float) : 0;
 }
 
+template <int WM>
+static int launch_tiles(const TilePlan &p, int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
+                        const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t stream)
+{
+    constexpr int FULLN = (4 / WM) * 128;
+    const int tn = (N + FULLN - 1) / FULLN;
+    if (p.ksplit >= 2) {
+        if ((size_t)p.ksplit * M * N * sizeof(float) > ws.partial_bytes) return SQP_ERR_WORKSPACE;
+        float *part = ws.partial;
+        w4a16_prefill_kernel<2, WM><<<dim3((unsigned)p.half, p.ksplit), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, part, epi);
+        const long total8 = (long)M * N / 8;
+        splitk_reduce_kernel<<<(unsigned)((total8 + 255) / 256), 256, 0, stream>>>(part, total8, (long)M * N, p.ksplit, y, epi);
+        return sqp_launch_status();
+    }
+    if (p.full > 0)
+        w4a16_prefill_kernel<4, WM><<<dim3((unsigned)p.full), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, nullptr, epi);
+    if (p.half > 0)
+        w4a16_prefill_kernel<2, WM><<<dim3((unsigned)p.half), 256, 0, stream>>>(M, N, K, group, (int)p.full, tn, x, packed, scales, zeros, y, nullptr, epi);
+    return sqp_launch_status();
+}
+
 int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
                      const h16 *scales, const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t stream)
 {
     if (group % BK == 0) {
-        const int tn = (N + 255) / 256;
-        TilePlan p = plan_tiles(M, N, K, compute_units(), ws.partial != nullptr);
-        if (p.ksplit >= 2) {
-            if ((size_t)p.ksplit * M * N * sizeof(float) > ws.partial_bytes) return SQP_ERR_WORKSPACE;
-            float *part = ws.partial;
-            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)p.half, p.ksplit), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, part, epi);
-            const long total8 = (long)M * N / 8;
-            splitk_reduce_kernel<<<(unsigned)((total8 + 255) / 256), 256, 0, stream>>>(part, total8, (long)M * N, p.ksplit, y, epi);
-            return sqp_launch_status();
-        }
-        if (p.full > 0)
-            w4a16_prefill_kernel<MAIN_NT, MAIN_W><<<dim3((unsigned)p.full), MAIN_W * 64, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, nullptr, epi);
-        if (p.half > 0)
-            w4a16_prefill_kernel<2, 4><<<dim3((unsigned)p.half), 256, 0, stream>>>(M, N, K, group, (int)p.full, tn, x, packed, scales, zeros, y, nullptr, epi);
-        return sqp_launch_status();
+        const TilePlan p = plan_tiles(M, N, K, compute_units(), ws.partial != nullptr);
+        if (p.wm == 1) return launch_tiles<1>(p, M, N, K, group, x, packed, scales, zeros, y, epi, ws, stream);
+        return launch_tiles<2>(p, M, N, K, group, x, packed, scales, zeros, y, epi, ws, stream);
     }
     // group sizes the tiled kernel does not cover
     return decode_in_row_blocks(M, N, K, group, x, packed, scales, zeros, y, epi, ws, stream);

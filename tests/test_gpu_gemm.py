@@ -145,30 +145,36 @@ def _layer_cached(orc, M, K, N, shape_idx):
     (129, 512, 136, 256), (100, 128, 64, 32), (257, 192, 8, 64), (512, 2048, 1000, 128),
     (130, 1024, 264, 1024)])
 @pytest.mark.parametrize("tiles", [0, 1, 2])
-def test_prefill_shapes(orc, sqp, M, K, N, group, tiles):
+@pytest.mark.parametrize("shape", [1, 2])
+def test_prefill_shapes(orc, sqp, M, K, N, group, tiles, shape):
     """Tiled matrix-core path: full-output parity on shapes spanning several tiles with
     ragged edges in M and N, several group sizes (32 takes the fallback path); with the
-    automatic tile choice, with 256-column tiles only and with 128-column tiles only."""
-    print("case prefill", M, K, N, group, tiles, flush=True)
+    automatic tile choice, with full tiles only and with half-width tiles only; for both
+    full-tile shapes (1: 128 x 512, 2: 256 x 256)."""
+    print("case prefill", M, K, N, group, tiles, shape, flush=True)
     xs, p, sc, z = _layer(orc, M, K, N, group)
     L = sqp.lib()
     L.sqp_debug_set_prefill_tiles(tiles)
+    L.sqp_debug_set_prefill_shape(shape)
     try:
         _check(orc, sqp, xs, p, sc, z, group)
     finally:
         L.sqp_debug_set_prefill_tiles(0)
+        L.sqp_debug_set_prefill_shape(0)
 
 
 @pytest.mark.parametrize("M,K,N,group,ksplit", [
     (300, 1024, 520, 128, 2), (300, 1024, 520, 128, 3), (65, 256, 264, 128, 2), (130, 384, 72, 64, 3),
     (129, 512, 136, 256, 4), (257, 1024, 264, 128, 16), (300, 1024, 520, 1024, 3)])
-def test_prefill_k_split(orc, sqp, M, K, N, group, ksplit):
+@pytest.mark.parametrize("shape", [1, 2])
+def test_prefill_k_split(orc, sqp, M, K, N, group, ksplit, shape):
     """Tiled path with K split across workgroups (fp32 partial matrices added in part order):
     parts that start inside a quantisation group, ragged M and N; twice, bit-identical."""
-    print("case prefill ksplit", M, K, N, group, ksplit, flush=True)
+    print("case prefill ksplit", M, K, N, group, ksplit, shape, flush=True)
     xs, p, sc, z = _layer(orc, M, K, N, group)
     L = sqp.lib()
     L.sqp_debug_set_prefill_ksplit(ksplit)
+    L.sqp_debug_set_prefill_shape(shape)
     try:
         y_ref, t_ref = orc.w4a16_gemm_ref(xs, p, sc, z, group)
         args = (dev(xs), dev(p), dev(sc), dev(z), group)
@@ -176,6 +182,7 @@ def test_prefill_k_split(orc, sqp, M, K, N, group, ksplit):
         y2 = host(sqp.w4a16_gemm(*args))
     finally:
         L.sqp_debug_set_prefill_ksplit(-1)
+        L.sqp_debug_set_prefill_shape(0)
     assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
     ok, worst, nbad = gemm_tolerance_ok(orc, y, y_ref, t_ref)
     assert ok, "worst err/tol %.3f, %d elements out of tolerance" % (worst, nbad)

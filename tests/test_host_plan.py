@@ -82,29 +82,42 @@ def test_decode_plan_small_model_values(L):
     assert _decode_plan(L, 16, 22016, 4096, 128)[:2] == (4, 2)     # 86 tiles: 172 workgroups, not 258
 
 
-def test_tile_plan_invariants(L):
-    for M in (65, 128, 256, 300, 512, 1024, 2048, 4096):
-        for (K, N) in wl.MODEL_SHAPES["34b"] + [(1024, 264), (256, 8), (8192, 256)]:
-            for cus in (256, 304, 64):
-                full, half, ks = _tile_plan(L, M, N, K, cus)
-                tiles = -(-N // 256) * -(-M // 256)
-                assert full >= 0 and half >= 0 and ks >= 1
-                assert full + half // 2 == tiles and half % 2 == 0   # every tile exactly once
-                if ks >= 2:
-                    assert full == 0 and 4 * tiles <= cus
-                    assert half * ks <= cus                          # one round
-                    assert K // 64 // ks >= 8                        # at least 8 stages per part
-                    assert ks * M * N * 4 <= 128 << 20               # fits the workspace
-                else:
-                    assert full % cus == 0 or half == 0              # first launch: whole rounds only
-                    assert half <= cus                               # the remainder is one round
+@pytest.mark.parametrize("shape", [1, 2])
+def test_tile_plan_invariants(L, shape):
+    """Both full-tile shapes (1: 128 x 512, 2: 256 x 256)."""
+    bm, bn = (128, 512) if shape == 1 else (256, 256)
+    L.sqp_debug_set_prefill_shape(shape)
+    try:
+        for M in (65, 128, 256, 300, 512, 1024, 2048, 4096):
+            for (K, N) in wl.MODEL_SHAPES["34b"] + [(1024, 264), (256, 8), (8192, 256)]:
+                for cus in (256, 304, 64):
+                    full, half, ks = _tile_plan(L, M, N, K, cus)
+                    tiles = -(-N // bn) * -(-M // bm)
+                    assert full >= 0 and half >= 0 and ks >= 1
+                    assert full + half // 2 == tiles and half % 2 == 0   # every tile exactly once
+                    if ks >= 2:
+                        assert full == 0 and 4 * tiles <= cus
+                        assert half * ks <= cus                          # one round
+                        assert K // 64 // ks >= 8                        # at least 8 stages per part
+                    else:
+                        assert full % cus == 0 or half == 0              # first launch: whole rounds only
+                        assert half <= cus                               # the remainder is one round
+    finally:
+        L.sqp_debug_set_prefill_shape(0)
 
 
 def test_tile_plan_bench_shapes(L):
-    assert _tile_plan(L, 2048, 8192, 8192) == (256, 0, 1)
-    assert _tile_plan(L, 2048, 10240, 8192) == (256, 128, 1)
-    assert _tile_plan(L, 2048, 44032, 8192) == (1280, 192, 1)
-    assert _tile_plan(L, 256, 8192, 8192) == (0, 64, 4)
+    """The tile counts of the benchmark's M = 2048 launches are the same for both shapes."""
+    for shape in (0, 1, 2):
+        L.sqp_debug_set_prefill_shape(shape)
+        try:
+            assert _tile_plan(L, 2048, 8192, 8192) == (256, 0, 1)
+            assert _tile_plan(L, 2048, 10240, 8192) == (256, 128, 1)
+            assert _tile_plan(L, 2048, 44032, 8192) == (1280, 192, 1)
+            assert _tile_plan(L, 4096, 8192, 22016) == (512, 0, 1)
+            assert _tile_plan(L, 256, 8192, 8192) == (0, 64, 4)
+        finally:
+            L.sqp_debug_set_prefill_shape(0)
 
 
 def test_quant_loss_argument_errors(L):
