@@ -25,10 +25,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2516.6
 
-# HBM bytes per decode launch (averaged over the four shapes of the sweep) from the
-# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/w4a16_decode_34b_m16_hbm_traffic.md (34B shapes, M=16, default plan).
+# HBM bytes per decode launch (averaged over the four shapes of the sweep) from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs summarised in the profile file below (34B shapes, M=16).  The
+# figure belongs to the launch plans listed with it: if the library picks another plan for one
+# of these shapes the figure is stale and the run stops, so that the profile gets refreshed.
+TRAFFIC_PROFILE = "profiles/w4a16_decode_34b_m16_hbm_traffic.md"
 TRAFFIC_BYTES_PER_LAUNCH = 109.4e6
+TRAFFIC_PLANS = {(8192, 10240): (4, 6), (8192, 8192): (2, 4), (8192, 44032): (4, 4), (22016, 8192): (4, 8)}  # (strips, K parts)
 
 
 def parse():
@@ -101,6 +104,18 @@ def main():
     torch.cuda.synchronize()
     t_build = time.time() - t_build
 
+    traffic = None
+    if args.model == "34b" and M == 16:
+        import ctypes
+        L = sqp.lib()
+        for (K, N) in shapes:
+            nw, split, kspg = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+            L.sqp_debug_decode_plan(M, N, K, G, ctypes.byref(nw), ctypes.byref(split), ctypes.byref(kspg))
+            if (nw.value, split.value) != TRAFFIC_PLANS[(K, N)]:
+                sys.exit("bench.py: the launch plan of %d->%d is now %s, but %s was taken with %s: refresh the profile and "
+                         "TRAFFIC_* in bench.py" % (K, N, (nw.value, split.value), TRAFFIC_PROFILE, TRAFFIC_PLANS[(K, N)]))
+        traffic = TRAFFIC_BYTES_PER_LAUNCH
+
     launches_per_step = nlayers * len(shapes)
     bytes_per_step = nlayers * sum(wl.algorithmic_bytes(M, N, K, G) for (K, N) in shapes)
 
@@ -124,7 +139,7 @@ def main():
 
     # the library allocates nothing: hand it a workspace for its split launches that covers
     # every shape of this run (decode rows of the sweep, the side measurements' M = 1 and 2048)
-    ws_need = max(sqp.workspace_bytes(m, N, K, G) for (K, N) in shapes for m in (1, M, 16, 2048, 4096))
+    ws_need = max(sqp.workspace_bytes(m, N, K, G) for (K, N) in shapes for m in (1, M, 16, 32, 64, 65, 128, 256, 2048, 4096))
     sqp.set_workspace(max(ws_need, 64 << 20))
     torch.cuda.synchronize()
     graph = None
@@ -158,17 +173,19 @@ def main():
     achieved = bytes_per_launch / avg_launch_s / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": TRAFFIC_BYTES_PER_LAUNCH if (args.model == "34b" and M == 16) else None,
+                "traffic": traffic, "traffic_source": TRAFFIC_PROFILE if traffic else None,
                 "kernel": "w4a16_decode_kernel", "avg_launch_us": round(avg_launch_s * 1e6, 2),
                 "algorithmic_bytes_per_launch": round(bytes_per_launch)}
 
-    extra = {}
+    extra, roofline_prefill = {}, None
     if not args.no_extra:
-        extra = side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, G)
+        extra, roofline_prefill = side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, G, M)
 
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(np, torch, wl, shapes, layers, xs, M, G)
+        if not args.no_extra:
+            cpu["other_kernels"] = cpu_baseline_other(np, torch, sqp, wl, dev, shapes, layers, s_first, activation, G, extra)
 
     out = {
         "metric": "W4A16 GEMM: HBM GB/s at M<=16 (% of peak); TFLOP/s at M=2048 (% MFMA)",
@@ -181,6 +198,7 @@ def main():
                    "build_s": round(t_build, 1)},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
         "roofline": roofline,
+        "roofline_prefill": roofline_prefill,
         "cpu_baseline": cpu,
         "extra": extra,
     }
@@ -199,10 +217,42 @@ def _time(torch, fn, iters):
     return e0.elapsed_time(e1) * 1e-3 / iters
 
 
-def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, G):
-    """Context figures outside the headline: M=1 decode sweep, prefill at M=2048 (TFLOP/s
-    against the fp16 MFMA peak) and the companion kernels on the 22016x8192 weight."""
+def _graph_time(torch, fn, iters):
+    """Seconds per call of fn when fn's launches are replayed from a HIP graph."""
+    fn()
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            fn()
+    torch.cuda.synchronize()
+    return _time(torch, graph.replay, iters)
+
+
+def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, G, M_decode):
+    """Context figures outside the headline: the decode sweep by layer shape and at M=1, the
+    tiled path at M=2048 and 4096 (TFLOP/s against the fp16 MFMA peak: the second half of the
+    metric, returned as its own roofline object), the row counts around the switch between the
+    two paths, on-chip reference rates (plain copy, plain read, MFMA-only loop) and the
+    companion kernels on the 22016x8192 weight."""
+    import ctypes
     extra = {}
+    L = sqp.lib()
+    # the headline sweep, one layer shape at a time (graph replay over the resident layers)
+    by_shape = {}
+    for si, (K, N) in enumerate(shapes):
+        x = sqp.smooth_apply_x(activation(M_decode, K, 2000 + M_decode), s_first[si])
+        y = torch.empty((M_decode, N), device=dev, dtype=torch.float16)
+
+        def sweep_one():
+            for per in layers:
+                p, sc, z = per[si]
+                sqp.w4a16_gemm(x, p, sc, z, G, out=y)
+        t = _graph_time(torch, sweep_one, 5) / len(layers)
+        b = wl.algorithmic_bytes(M_decode, N, K, G)
+        by_shape["%dx%d" % (K, N)] = {"us": round(t * 1e6, 2), "gbs": round(b / t / 1e9, 1), "pct_hbm_peak": round(100 * b / t / 1e9 / HBM_PEAK_GBS, 1)}
+    extra["decode_m%d_by_shape" % M_decode] = by_shape
     # decode at M=1 over all resident layers
     M = 1
     xs = [sqp.smooth_apply_x(activation(M, K, 2000 + M), s_first[si]) for si, (K, N) in enumerate(shapes)]
@@ -212,37 +262,77 @@ def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, 
         for per in layers:
             for si, (p, sc, z) in enumerate(per):
                 sqp.w4a16_gemm(xs[si], p, sc, z, G, out=ys[si])
-    t = _time(torch, sweep, 3)
+    t = _graph_time(torch, sweep, 3)
     b = len(layers) * sum(wl.algorithmic_bytes(M, N, K, G) for (K, N) in shapes)
     extra["decode_m1_gbs"] = round(b / t / 1e9, 1)
     extra["decode_m1_pct_hbm_peak"] = round(100 * b / t / 1e9 / HBM_PEAK_GBS, 2)
-    # prefill, M = 2048, the four shapes, rotating over the resident layers
-    M = 2048
-    pre = {}
-    flops_total, t_total = 0.0, 0.0
-    for si, (K, N) in enumerate(shapes):
-        x = sqp.smooth_apply_x(activation(M, K, 2000 + M), s_first[si])
-        y = torch.empty((M, N), device=dev, dtype=torch.float16)
-        nl = min(len(layers), 8)
-        state = {"i": 0}
+    # the tiled path at M = 2048 and 4096, the four shapes, rotating over resident layers; the
+    # average launch duration comes from HIP events around the timed launches
+    roofline_prefill = None
+    for M in (2048, 4096):
+        pre = {}
+        flops_total, t_total = 0.0, 0.0
+        for si, (K, N) in enumerate(shapes):
+            x = sqp.smooth_apply_x(activation(M, K, 2000 + M), s_first[si])
+            y = torch.empty((M, N), device=dev, dtype=torch.float16)
+            nl = min(len(layers), 8)
+            state = {"i": 0}
 
-        def one():
-            p, sc, z = layers[state["i"] % nl][si]
-            state["i"] += 1
-            sqp.w4a16_gemm(x, p, sc, z, G, out=y)
-        t = _time(torch, one, nl)
-        fl = wl.gemm_flops(M, N, K)
-        pre["%dx%d" % (K, N)] = round(fl / t / 1e12, 1)
-        flops_total += fl
-        t_total += t
-        del x, y
-    extra["prefill_m2048_tflops_by_shape"] = pre
-    extra["prefill_m2048_tflops"] = round(flops_total / t_total / 1e12, 1)
-    extra["prefill_m2048_pct_mfma_peak"] = round(100 * flops_total / t_total / 1e12 / MFMA_F16_PEAK_TFLOPS, 2)
+            def one():
+                p, sc, z = layers[state["i"] % nl][si]
+                state["i"] += 1
+                sqp.w4a16_gemm(x, p, sc, z, G, out=y)
+            t = _time(torch, one, nl)
+            fl = wl.gemm_flops(M, N, K)
+            pre["%dx%d" % (K, N)] = {"tflops": round(fl / t / 1e12, 1), "avg_launch_us": round(t * 1e6, 1),
+                                     "pct_mfma_peak": round(100 * fl / t / 1e12 / MFMA_F16_PEAK_TFLOPS, 1)}
+            flops_total += fl
+            t_total += t
+            del x, y
+        agg = flops_total / t_total / 1e12
+        obj = {"bound": "mfma", "achieved": round(agg, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+               "frac": round(agg / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None, "kernel": "w4a16_prefill_kernel",
+               "workload": "34B shapes at M=%d, one call per shape and layer, flops 2MNK" % M, "by_shape": pre}
+        if M == 2048:
+            roofline_prefill = obj
+            extra["prefill_m2048_tflops"] = round(agg, 1)
+            extra["prefill_m2048_pct_mfma_peak"] = round(100 * agg / MFMA_F16_PEAK_TFLOPS, 2)
+        else:
+            roofline_prefill["m4096"] = {k: obj[k] for k in ("achieved", "frac", "by_shape")}
+    # where the two paths meet: one 34B shape (8192 -> 8192) at row counts around the switch at 64
+    K, N = shapes[1]
+    cross = {}
+    for M in (16, 32, 64, 65, 128, 256):
+        x = sqp.smooth_apply_x(activation(M, K, 2000 + M), s_first[1])
+        y = torch.empty((M, N), device=dev, dtype=torch.float16)
+
+        def sweep_m():
+            for per in layers[:16]:
+                p, sc, z = per[1]
+                sqp.w4a16_gemm(x, p, sc, z, G, out=y)
+        cross["m%d_us" % M] = round(_graph_time(torch, sweep_m, 5) / 16 * 1e6, 2)
+    extra["crossover_8192x8192_us"] = cross
+    # on-chip reference rates: the plain copy kernel that calibrates the traffic counters and a
+    # plain streaming read with and without the non-temporal hint, 2 GiB each
+    L.sqp_debug_plain_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.sqp_debug_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    big = torch.zeros(1 << 29, dtype=torch.float32, device=dev)
+    dst = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    sink4 = torch.zeros(4, dtype=torch.int32, device=dev)
+    stq = torch.cuda.current_stream().cuda_stream
+
+    def copy1():
+        assert L.sqp_debug_plain_copy(big.data_ptr(), dst.data_ptr(), dst.numel() * 4, stq) == 0
+    t = _time(torch, copy1, 5)
+    extra["plain_copy_gbs_read_plus_write"] = round(2.0 * dst.numel() * 4 / t / 1e9, 1)
+    for nt in (0, 1):
+        def read1():
+            assert L.sqp_debug_read_probe(big.data_ptr(), big.numel() * 4, nt, sink4.data_ptr(), stq) == 0
+        t = _time(torch, read1, 5)
+        extra["read_probe_%s_gbs" % ("nt" if nt else "plain")] = round(big.numel() * 4 / t / 1e9, 1)
+    del big, dst
     # what the matrix cores sustain on this chip with nothing else to do: a loop of independent
     # 32x32x16 fp16 MFMAs on one of the activations above (the clock settles under the power limit)
-    import ctypes
-    L = sqp.lib()
     L.sqp_debug_mfma_ceiling.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     data = sqp.smooth_apply_x(activation(16, shapes[0][0], 2016), s_first[0])  # >= 64 KiB of smoothed activations
     blocks, iters = 256, 20000
@@ -375,7 +465,7 @@ def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, 
             dense["%dx%d_m%d_us" % (Kd, Nd, Md)] = round(t * 1e6, 1)
         del ws
     extra["dense_fp16_vendor_gemm"] = dense
-    return extra
+    return extra, roofline_prefill
 
 
 def cpu_baseline(np, torch, wl, shapes, layers, xs, M, G):
@@ -399,6 +489,42 @@ def cpu_baseline(np, torch, wl, shapes, layers, xs, M, G):
     return {"value": round(b_total / t_total / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": "layers 0..%d of the same sweep (all 4 linears, M=%d), one call each: %.1f s of CPU time" %
                       (nl - 1, M, t_total)}
+
+
+def cpu_baseline_other(np, torch, sqp, wl, dev, shapes, layers, s_first, activation, G, extra):
+    """The oracle's companion functions on the same 22016 x 8192 weight the GPU figures in
+    `extra` are quoted on, and its GEMM on 32 sampled rows of the M = 2048 call of 8192 -> 8192
+    (extrapolated to 2048 rows: every row costs the same)."""
+    import oracle
+    out = {}
+    K, N = shapes[3]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    w = (torch.randn((K, N), device=dev, generator=gen, dtype=torch.float32) * 0.02).half().cpu().numpy()
+    xcal = activation(wl.T_CAL, K, 3000).cpu().numpy()
+    t0 = time.perf_counter()
+    oracle.smooth_scales(xcal, w, wl.ALPHA)
+    t = time.perf_counter() - t0
+    out["smooth_scales_22016x8192"] = {"oracle_s": round(t, 2), "gpu_us": extra.get("smooth_scales_22016x8192_us"),
+                                       "oracle_gbs": round((2.0 * K * N + 2.0 * wl.T_CAL * K) / t / 1e9, 2)}
+    t0 = time.perf_counter()
+    oracle.quantize_pack(w, G)
+    t = time.perf_counter() - t0
+    out["quantize_pack_22016x8192"] = {"oracle_s": round(t, 2), "gpu_us": extra.get("quantize_pack_22016x8192_us"),
+                                       "oracle_gbs": round((2.0 * K * N + K * N * (0.5 + 3.0 / G)) / t / 1e9, 2)}
+    del w
+    K, N = shapes[1]
+    p, sc, z = layers[0][1]
+    rows = 32
+    x = sqp.smooth_apply_x(activation(2048, K, 2000 + 2048), s_first[1])[:rows].contiguous().cpu().numpy()
+    pn, scn, zn = p.cpu().numpy().view(np.uint32), sc.cpu().numpy(), z.cpu().numpy()
+    t0 = time.perf_counter()
+    oracle.w4a16_gemm_f32(x, pn, scn, zn, G)
+    t = time.perf_counter() - t0
+    out["gemm_8192x8192_m2048"] = {"oracle_s_for_32_rows": round(t, 2), "oracle_tflops_extrapolated": round(wl.gemm_flops(rows, N, K) / t / 1e12, 5),
+                                   "sample": "32 of 2048 rows, time x 64"}
+    out["cores"] = oracle.num_threads()
+    return out
 
 
 if __name__ == "__main__":

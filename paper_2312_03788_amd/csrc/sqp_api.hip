@@ -32,6 +32,35 @@ extern "C" int sqp_debug_plain_copy(const void *src, void *dst, size_t bytes, vo
     return sqp_launch_status();
 }
 
+// Plain streaming read (16 bytes per lane, eight loads in flight per lane, grid-stride), with or
+// without the non-temporal hint: the read bandwidth the chip reaches with nothing else to do,
+// the reference the weight-streaming GEMM is measured against beside the published peak.
+// Benchmark hook, not part of the ABI.
+typedef uint32_t probe_u32x4 __attribute__((ext_vector_type(4)));
+template <bool NT>
+__global__ void __launch_bounds__(256) read_probe_kernel(const probe_u32x4 *__restrict__ src, size_t n, uint32_t *__restrict__ sink)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    uint32_t acc = 0;
+    for (; i + 7 * stride < n; i += 8 * stride) {
+        probe_u32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = NT ? __builtin_nontemporal_load(src + i + j * stride) : src[i + j * stride];
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;  // keeps the loads alive; practically never taken
+}
+extern "C" int sqp_debug_read_probe(const void *src, size_t bytes, int nt, void *sink, void *stream)
+{
+    if (!src || !sink || (bytes & 15)) return SQP_ERR_SHAPE;
+    const size_t n = bytes / 16;
+    if (nt) read_probe_kernel<true><<<4096, 256, 0, (hipStream_t)stream>>>((const probe_u32x4 *)src, n, (uint32_t *)sink);
+    else read_probe_kernel<false><<<4096, 256, 0, (hipStream_t)stream>>>((const probe_u32x4 *)src, n, (uint32_t *)sink);
+    return sqp_launch_status();
+}
+
 // A loop of nothing but independent 32x32x16 fp16 MFMAs (16 accumulator tiles per wave, four
 // waves per workgroup, operands taken from `data`): the rate the matrix cores sustain on this
 // chip for the given operand values, i.e. the ceiling the tiled GEMM is measured against

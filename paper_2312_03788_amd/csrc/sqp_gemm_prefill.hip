@@ -44,7 +44,10 @@ constexpr int BK = 64;
 //           the K-split launches.
 // Workgroup b of the launch handles tile tile0 + b / (full columns / columns) of the tn x tm grid
 // of full tiles (column index fastest), column half b % 2 of it when it covers half.
-template <int NT, int WM>
+// G32: quantisation groups of 32 rows, i.e. two groups per 64-row stage (the steps and zero
+// points of both are loaded per stage and the unpack switches sets after the second k-step);
+// otherwise the group is a multiple of 64 rows.
+template <int NT, int WM, bool G32>
 __global__ void __launch_bounds__(256)
 w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h16 *__restrict__ x,
                      const uint32_t *__restrict__ packed, const h16 *__restrict__ scales,
@@ -63,7 +66,8 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     constexpr int OX = (BM / 8) / W;       // direct loads per wave per stage (one per 1 KB block)
     constexpr int WGN = WNW * WN;          // columns per workgroup: a full tile's or half of them
     static_assert(OX % 4 == 0, "the loads of a stage are spread evenly over its four k-steps");
-    constexpr int OW = 4 + 2;
+    constexpr int NQ = G32 ? 2 : 1;        // quantisation groups per stage
+    constexpr int OW = 4 + 2 * NQ;
     __shared__ __attribute__((aligned(1024))) unsigned char xring[XD * XSTAGE];
 
     const int lane = threadIdx.x & 63;
@@ -79,7 +83,7 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     const int stages_all = K / BK;
     const int stage0 = (int)((long)stages_all * blockIdx.y / gridDim.y);
     const int stages = (int)((long)stages_all * (blockIdx.y + 1) / gridDim.y) - stage0;
-    const int spg = group / BK;            // stages per quantisation group
+    const int spg = G32 ? 1 : group / BK;  // stages per quantisation group (G32: two groups per stage)
 
     int ncol = n0 + NT * l32;
     if (ncol >= N) ncol = 0;
@@ -95,8 +99,8 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
 
     struct Stage {
         wvec w[4];    // per k-step: packed words of the lane's NT columns
-        scvec sc;     // NT fp16 steps
-        uint32_t zr;  // NT zero points, one byte each
+        scvec sc[NQ];     // NT fp16 steps (per group of the stage)
+        uint32_t zr[NQ];  // NT zero points, one byte each
     };
 
     // The loading side walks the stages with wave-uniform byte pointers that are advanced by
@@ -104,8 +108,9 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     // stages of the branch-free loop re-read the last one (cache hits).
     const long wrow2 = (long)N * 8;        // two packed rows (one k-step) in bytes
     const unsigned char *wq = reinterpret_cast<const unsigned char *>(packed) + (long)stage0 * 4 * wrow2;
-    const unsigned char *sq = reinterpret_cast<const unsigned char *>(scales) + (long)(stage0 / spg) * N * 2;
-    const unsigned char *zq = zeros + (long)(stage0 / spg) * N;
+    const long prow = G32 ? (long)stage0 * 2 : (long)(stage0 / spg);  // first parameter row of this workgroup
+    const unsigned char *sq = reinterpret_cast<const unsigned char *>(scales) + prow * N * 2;
+    const unsigned char *zq = zeros + prow * N;
     const unsigned char *xq = reinterpret_cast<const unsigned char *>(x) + (long)stage0 * (BK * 2);
     int ist = 0, kin = stage0 % spg;        // stage being issued (relative), its position inside its group
     const uint32_t voff_w = (uint32_t)(kb * N + ncol) * 4u;
@@ -119,20 +124,27 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
             else
                 asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.w[ks]) : "v"(voff_w), "s"(base) : "memory");
         }
-        if constexpr (NT == 4) {
-            asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sq) : "memory");
-            asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zq) : "memory");
-        } else {
-            asm volatile("global_load_dword %0, %1, %2" : "=v"(s.sc) : "v"(voff_s), "s"(sq) : "memory");
-            asm volatile("global_load_ushort %0, %1, %2" : "=v"(s.zr) : "v"(voff_z), "s"(zq) : "memory");
+#pragma unroll
+        for (int g = 0; g < NQ; g++) {
+            const unsigned char *sg = sq + (long)g * N * 2, *zg = zq + (long)g * N;  // wave-uniform
+            if constexpr (NT == 4) {
+                asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(s.sc[g]) : "v"(voff_s), "s"(sg) : "memory");
+                asm volatile("global_load_dword %0, %1, %2" : "=v"(s.zr[g]) : "v"(voff_z), "s"(zg) : "memory");
+            } else {
+                asm volatile("global_load_dword %0, %1, %2" : "=v"(s.sc[g]) : "v"(voff_s), "s"(sg) : "memory");
+                asm volatile("global_load_ushort %0, %1, %2" : "=v"(s.zr[g]) : "v"(voff_z), "s"(zg) : "memory");
+            }
         }
     };
     auto landed = [&](Stage &s, auto after) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(after)::value) : "memory");
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) asm volatile("" : "+v"(s.w[ks]));
-        asm volatile("" : "+v"(s.sc));
-        asm volatile("" : "+v"(s.zr));
+#pragma unroll
+        for (int g = 0; g < NQ; g++) {
+            asm volatile("" : "+v"(s.sc[g]));
+            asm volatile("" : "+v"(s.zr[g]));
+        }
     };
 
     // Activations: wave w copies blocks w, w+4, ..., w+28 of the stage (a block = 8 rows x 128
@@ -163,8 +175,8 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
         kin += more ? 1 : 0;
         const bool wrap = kin == spg;
         kin = wrap ? 0 : kin;
-        sq += wrap ? (long)N * 2 : 0;
-        zq += wrap ? (long)N : 0;
+        sq += wrap ? (long)N * 2 * NQ : 0;
+        zq += wrap ? (long)N * NQ : 0;
     };
     const uint32_t xrd0 = (uint32_t)(size_t)xring +
                           (uint32_t)(((wm * 128 + l32) >> 3) * 1024 + ((wm * 128 + l32) & 7) * 128);
@@ -184,19 +196,22 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
 
     // per-stage constants of the unpack: -(1024 + Z), -(64 + Z) and the step, each in both
     // halves of a register; a stage past the end gets a step of 0 and adds nothing
-    h16x2 neg_hi[NT], neg_lo[NT], delta[NT];
+    // (one set per quantisation group of the stage)
+    h16x2 neg_hi[NQ][NT], neg_lo[NQ][NT], delta[NQ][NT];
     auto stage_consts = [&](const Stage &s, bool live) {
         const uint32_t sel_even = live ? 0x01000100u : 0x0c0c0c0cu;  // byte selectors of v_perm_b32
         const uint32_t sel_odd = live ? 0x03020302u : 0x0c0c0c0cu;   // (0x0c selects a zero byte)
 #pragma unroll
-        for (int t = 0; t < NT; t++) {
-            const uint32_t z = (s.zr >> (8 * t)) & 0xffu;
-            neg_hi[t] = neg_hi_of(z);
-            neg_lo[t] = neg_lo_of(z);
-            uint32_t sw;
-            if constexpr (NT == 4) sw = s.sc[t >> 1]; else sw = s.sc;
-            delta[t] = __builtin_bit_cast(h16x2, __builtin_amdgcn_perm(sw, sw, (t & 1) ? sel_odd : sel_even));
-        }
+        for (int g = 0; g < NQ; g++)
+#pragma unroll
+            for (int t = 0; t < NT; t++) {
+                const uint32_t z = (s.zr[g] >> (8 * t)) & 0xffu;
+                neg_hi[g][t] = neg_hi_of(z);
+                neg_lo[g][t] = neg_lo_of(z);
+                uint32_t sw;
+                if constexpr (NT == 4) sw = s.sc[g][t >> 1]; else sw = s.sc[g];
+                delta[g][t] = __builtin_bit_cast(h16x2, __builtin_amdgcn_perm(sw, sw, (t & 1) ? sel_odd : sel_even));
+            }
     };
 
     // One continuous software pipeline over all k-steps.  While the 16 MFMAs of a k-step
@@ -249,9 +264,11 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     constexpr int NMF = 4 * NT;                 // MFMAs per k-step
     constexpr int WAIT_AT = NT == 4 ? 13 : 5;   // the LDS wait goes in front of this MFMA
 
-    // one entry j of group g; wn = the packed words of the next k-step
-    auto valu = [&](int g, int j, int cur, const wvec &wn) {
+    // one entry j of group g; wn = the packed words of the next k-step, kn = that k-step's
+    // position in its stage (it selects the quantisation group's constants)
+    auto valu = [&](int g, int j, int cur, const wvec &wn, int kn) {
         const int nxt = cur ^ 1;
+        const int qs = G32 ? (kn >> 1) : 0;
         if (g == G_P1) perm4(aq[1], xa[cur][1], j);
         else if (g == G_P2) perm4(aq[0], xa[cur][2], j);
         else if (g == G_P3) perm4(aq[1], xa[cur][3], j);
@@ -264,11 +281,11 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
             else       asm volatile("v_and_or_b32 %0, %1, %2, %3" : "=v"(bq[nxt][t][j]) : "v"(j < 2 ? wn[t] : w8[t]), "v"(uc.mask_lo), "v"(uc.magic_lo));
         } else if (g < G_MUL) {
             const int t = g - G_ADD;
-            if (j & 1) asm volatile("v_pk_add_f16 %0, %0, %1" : "+v"(bq[nxt][t][j]) : "v"(neg_lo[t]));
-            else       asm volatile("v_pk_add_f16 %0, %0, %1" : "+v"(bq[nxt][t][j]) : "v"(neg_hi[t]));
+            if (j & 1) asm volatile("v_pk_add_f16 %0, %0, %1" : "+v"(bq[nxt][t][j]) : "v"(neg_lo[qs][t]));
+            else       asm volatile("v_pk_add_f16 %0, %0, %1" : "+v"(bq[nxt][t][j]) : "v"(neg_hi[qs][t]));
         } else {
             const int t = g - G_MUL;
-            asm volatile("v_pk_mul_f16 %0, %0, %1" : "+v"(bq[nxt][t][j]) : "v"(delta[t]));
+            asm volatile("v_pk_mul_f16 %0, %0, %1" : "+v"(bq[nxt][t][j]) : "v"(delta[qs][t]));
         }
     };
 
@@ -287,7 +304,7 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
     // first operands of the pipeline, by the ordinary helpers
 #pragma unroll
     for (int t = 0; t < NT; t++) {
-        const u32x4 bw = __builtin_bit_cast(u32x4, dequant_word_scaled(stg[0].w[0][t], neg_hi[t], neg_lo[t], delta[t], uc));
+        const u32x4 bw = __builtin_bit_cast(u32x4, dequant_word_scaled(stg[0].w[0][t], neg_hi[0][t], neg_lo[0][t], delta[0][t], uc));
         bq[0][t][0] = bw.x; bq[0][t][1] = bw.y; bq[0][t][2] = bw.z; bq[0][t][3] = bw.w;
     }
     wait_a(xa[0]);
@@ -329,7 +346,7 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
                     mfma(acc[i / NT][i % NT], aq[(i / NT) & 1], bq[cur][i % NT]);
 #pragma unroll
                     for (int e = i * (4 * NG) / NMF; e < (i + 1) * (4 * NG) / NMF; e++)
-                        valu(NT == 4 ? order4[e / 4] : order2[e / 4], e % 4, cur, wn);
+                        valu(NT == 4 ? order4[e / 4] : order2[e / 4], e % 4, cur, wn, (ks + 1) & 3);
                 }
             }
             // End of the last iteration.  (1) Drain the clamped look-ahead loads: their
@@ -345,8 +362,11 @@ w4a16_prefill_kernel(int M, int N, int K, int group, int tile0, int tn, const h1
                 for (int j = 0; j < D; j++) {
 #pragma unroll
                     for (int ks = 0; ks < 4; ks++) asm volatile("" ::"v"(stg[j].w[ks]));
-                    asm volatile("" ::"v"(stg[j].sc));
-                    asm volatile("" ::"v"(stg[j].zr));
+#pragma unroll
+                    for (int g = 0; g < NQ; g++) {
+                        asm volatile("" ::"v"(stg[j].sc[g]));
+                        asm volatile("" ::"v"(stg[j].zr[g]));
+                    }
                 }
                 asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
             }
@@ -483,9 +503,9 @@ struct TilePlan {
     int ksplit, wm;
 };
 
-static TilePlan plan_tiles(int M, int N, int K, int cus, bool have_workspace)
+static TilePlan plan_tiles(int M, int N, int K, int group, int cus, bool have_workspace)
 {
-    const int wm = g_tile_shape == 2 ? 2 : 1;
+    const int wm = (g_tile_shape == 2 && group != 32) ? 2 : 1;  // groups of 32: the 128 x 512 shape only
     const int bm = 128 * wm, fulln = (4 / wm) * 128;
     const int tn = (N + fulln - 1) / fulln, tm = (M + bm - 1) / bm;
     const long tiles = (long)tn * tm;
@@ -524,7 +544,7 @@ static TilePlan plan_tiles(int M, int N, int K, int cus, bool have_workspace)
 // Test hook: the plan for a shape on a chip of `cus` compute units (no launch, no GPU needed).
 extern "C" void sqp_debug_prefill_plan(int M, int N, int K, int cus, long *full, long *half, int *ksplit)
 {
-    const TilePlan p = plan_tiles(M, N, K, cus, true);
+    const TilePlan p = plan_tiles(M, N, K, 128, cus, true);
     *full = p.full;
     *half = p.half;
     *ksplit = p.ksplit;
@@ -532,12 +552,12 @@ extern "C" void sqp_debug_prefill_plan(int M, int N, int K, int cus, long *full,
 
 size_t sqp_gemm_prefill_partial_bytes(int M, int N, int K, int group)
 {
-    if (group % BK != 0) return sqp_gemm_decode_partial_bytes(M < 64 ? M : 64, N, K, group);  // row-block fallback
-    const TilePlan p = plan_tiles(M, N, K, compute_units(), true);
+    if (group % BK != 0 && !(group == 32 && K % BK == 0)) return sqp_gemm_decode_partial_bytes(M < 64 ? M : 64, N, K, group);  // row-block fallback
+    const TilePlan p = plan_tiles(M, N, K, group, compute_units(), true);
     return p.ksplit >= 2 ? (size_t)p.ksplit * M * N * sizeof(float) : 0;
 }
 
-template <int WM>
+template <int WM, bool G32>
 static int launch_tiles(const TilePlan &p, int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
                         const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t stream)
 {
@@ -546,26 +566,27 @@ static int launch_tiles(const TilePlan &p, int M, int N, int K, int group, const
     if (p.ksplit >= 2) {
         if ((size_t)p.ksplit * M * N * sizeof(float) > ws.partial_bytes) return SQP_ERR_WORKSPACE;
         float *part = ws.partial;
-        w4a16_prefill_kernel<2, WM><<<dim3((unsigned)p.half, p.ksplit), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, part, epi);
+        w4a16_prefill_kernel<2, WM, G32><<<dim3((unsigned)p.half, p.ksplit), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, part, epi);
         const long total8 = (long)M * N / 8;
         splitk_reduce_kernel<<<(unsigned)((total8 + 255) / 256), 256, 0, stream>>>(part, total8, (long)M * N, p.ksplit, y, epi);
         return sqp_launch_status();
     }
     if (p.full > 0)
-        w4a16_prefill_kernel<4, WM><<<dim3((unsigned)p.full), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, nullptr, epi);
+        w4a16_prefill_kernel<4, WM, G32><<<dim3((unsigned)p.full), 256, 0, stream>>>(M, N, K, group, 0, tn, x, packed, scales, zeros, y, nullptr, epi);
     if (p.half > 0)
-        w4a16_prefill_kernel<2, WM><<<dim3((unsigned)p.half), 256, 0, stream>>>(M, N, K, group, (int)p.full, tn, x, packed, scales, zeros, y, nullptr, epi);
+        w4a16_prefill_kernel<2, WM, G32><<<dim3((unsigned)p.half), 256, 0, stream>>>(M, N, K, group, (int)p.full, tn, x, packed, scales, zeros, y, nullptr, epi);
     return sqp_launch_status();
 }
 
 int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
                      const h16 *scales, const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t stream)
 {
-    if (group % BK == 0) {
-        const TilePlan p = plan_tiles(M, N, K, compute_units(), ws.partial != nullptr);
-        if (p.wm == 1) return launch_tiles<1>(p, M, N, K, group, x, packed, scales, zeros, y, epi, ws, stream);
-        return launch_tiles<2>(p, M, N, K, group, x, packed, scales, zeros, y, epi, ws, stream);
+    if (group % BK == 0 || (group == 32 && K % BK == 0)) {
+        const TilePlan p = plan_tiles(M, N, K, group, compute_units(), ws.partial != nullptr);
+        if (group == 32) return launch_tiles<1, true>(p, M, N, K, group, x, packed, scales, zeros, y, epi, ws, stream);  // one tile shape only
+        if (p.wm == 1) return launch_tiles<1, false>(p, M, N, K, group, x, packed, scales, zeros, y, epi, ws, stream);
+        return launch_tiles<2, false>(p, M, N, K, group, x, packed, scales, zeros, y, epi, ws, stream);
     }
-    // group sizes the tiled kernel does not cover
+    // group sizes the tiled kernel does not cover (neither a multiple of 64, nor 32 with K a multiple of 64)
     return decode_in_row_blocks(M, N, K, group, x, packed, scales, zeros, y, epi, ws, stream);
 }

@@ -143,7 +143,7 @@ def _layer_cached(orc, M, K, N, shape_idx):
 @pytest.mark.parametrize("M,K,N,group", [
     (65, 256, 264, 128), (256, 512, 256, 64), (300, 1024, 520, 128), (130, 384, 72, 64),
     (129, 512, 136, 256), (100, 128, 64, 32), (257, 192, 8, 64), (512, 2048, 1000, 128),
-    (130, 1024, 264, 1024)])
+    (130, 1024, 264, 1024), (300, 1024, 520, 32), (257, 192, 72, 32), (140, 96, 136, 32)])
 @pytest.mark.parametrize("tiles", [0, 1, 2])
 @pytest.mark.parametrize("shape", [1, 2])
 def test_prefill_shapes(orc, sqp, M, K, N, group, tiles, shape):
@@ -165,7 +165,7 @@ def test_prefill_shapes(orc, sqp, M, K, N, group, tiles, shape):
 
 @pytest.mark.parametrize("M,K,N,group,ksplit", [
     (300, 1024, 520, 128, 2), (300, 1024, 520, 128, 3), (65, 256, 264, 128, 2), (130, 384, 72, 64, 3),
-    (129, 512, 136, 256, 4), (257, 1024, 264, 128, 16), (300, 1024, 520, 1024, 3)])
+    (129, 512, 136, 256, 4), (257, 1024, 264, 128, 16), (300, 1024, 520, 1024, 3), (300, 1024, 520, 32, 3), (130, 512, 72, 32, 8)])
 @pytest.mark.parametrize("shape", [1, 2])
 def test_prefill_k_split(orc, sqp, M, K, N, group, ksplit, shape):
     """Tiled path with K split across workgroups (fp32 partial matrices added in part order):
