@@ -312,6 +312,19 @@ def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, 
                 sqp.w4a16_gemm(x, p, sc, z, G, out=y)
         cross["m%d_us" % M] = round(_graph_time(torch, sweep_m, 5) / 16 * 1e6, 2)
     extra["crossover_8192x8192_us"] = cross
+    # the fallback for group sizes the matrix-core kernels do not cover (one thread per output
+    # element): group 24 on a 3072 -> 4096 layer at M = 16, random codes
+    Kg, Ng, Gg = 3072, 4096, 24
+    gen_g = torch.Generator(device=dev)
+    gen_g.manual_seed(5)
+    pg = torch.randint(-2**31, 2**31 - 1, (Kg // 8, Ng), dtype=torch.int32, device=dev, generator=gen_g)
+    scg = (torch.rand((Kg // Gg, Ng), device=dev, generator=gen_g) * 0.004 + 0.003).half()
+    zg = torch.randint(0, 16, (Kg // Gg, Ng), dtype=torch.uint8, device=dev, generator=gen_g)
+    xg24 = torch.randn((16, Kg), device=dev, generator=gen_g).half()
+    yg24 = torch.empty((16, Ng), device=dev, dtype=torch.float16)
+    t = _time(torch, lambda: sqp.w4a16_gemm(xg24, pg, scg, zg, Gg, out=yg24), 10)
+    extra["generic_kernel_group24_3072x4096_m16_us"] = round(t * 1e6, 1)
+    del pg, scg, zg, xg24, yg24
     # on-chip reference rates: the plain copy kernel that calibrates the traffic counters and a
     # plain streaming read with and without the non-temporal hint, 2 GiB each
     L.sqp_debug_plain_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
