@@ -328,7 +328,7 @@ def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, 
     # on-chip reference rates: the plain copy kernel that calibrates the traffic counters and a
     # plain streaming read with and without the non-temporal hint, 2 GiB each
     L.sqp_debug_plain_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
-    L.sqp_debug_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    L.sqp_debug_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     big = torch.zeros(1 << 29, dtype=torch.float32, device=dev)
     dst = torch.empty(1 << 28, dtype=torch.float32, device=dev)
     sink4 = torch.zeros(4, dtype=torch.int32, device=dev)
@@ -338,9 +338,9 @@ def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, 
         assert L.sqp_debug_plain_copy(big.data_ptr(), dst.data_ptr(), dst.numel() * 4, stq) == 0
     t = _time(torch, copy1, 5)
     extra["plain_copy_gbs_read_plus_write"] = round(2.0 * dst.numel() * 4 / t / 1e9, 1)
-    for nt in (0, 1):
+    for nt in (0, 1):  # 768 workgroups = three per compute unit: the grid that reads fastest
         def read1():
-            assert L.sqp_debug_read_probe(big.data_ptr(), big.numel() * 4, nt, sink4.data_ptr(), stq) == 0
+            assert L.sqp_debug_read_probe(big.data_ptr(), big.numel() * 4, nt, 768, sink4.data_ptr(), stq) == 0
         t = _time(torch, read1, 5)
         extra["read_probe_%s_gbs" % ("nt" if nt else "plain")] = round(big.numel() * 4 / t / 1e9, 1)
     del big, dst

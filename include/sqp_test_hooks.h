@@ -36,9 +36,11 @@ void sqp_debug_prefill_plan(int M, int N, int K, int cus, long *full, long *half
  * instructions (data: 64 KiB of fp16 on the device, out: blocks * 256 floats; flops of the
  * launch = blocks * 4 * iters * 16 * 32768). */
 int sqp_debug_plain_copy(const void *src, void *dst, size_t bytes, void *stream);
-/* A plain streaming read of `bytes` (a multiple of 16; whole passes of 8 x 4096 x 256 x 16 bytes
- * are read, the rest is skipped), with (nt != 0) or without the non-temporal hint; sink: 4 bytes. */
-int sqp_debug_read_probe(const void *src, size_t bytes, int nt, void *sink, void *stream);
+/* A plain streaming read of `bytes` (a multiple of 16; whole passes of 8 x blocks x 256 x 16 bytes
+ * are read, the rest is skipped) by `blocks` workgroups of 256 threads, with (nt != 0) or without
+ * the non-temporal hint; sink: 4 bytes.  The rate depends on the grid: three workgroups per
+ * compute unit (768) read faster than thousands. */
+int sqp_debug_read_probe(const void *src, size_t bytes, int nt, int blocks, void *sink, void *stream);
 int sqp_debug_mfma_ceiling(const void *data, float *out, int blocks, int iters, void *stream);
 
 #pragma GCC visibility pop

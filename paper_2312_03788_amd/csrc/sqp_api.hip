@@ -52,12 +52,12 @@ __global__ void __launch_bounds__(256) read_probe_kernel(const probe_u32x4 *__re
     }
     if (acc == 0x9e3779b9u) sink[0] = acc;  // keeps the loads alive; practically never taken
 }
-extern "C" int sqp_debug_read_probe(const void *src, size_t bytes, int nt, void *sink, void *stream)
+extern "C" int sqp_debug_read_probe(const void *src, size_t bytes, int nt, int blocks, void *sink, void *stream)
 {
-    if (!src || !sink || (bytes & 15)) return SQP_ERR_SHAPE;
+    if (!src || !sink || (bytes & 15) || blocks <= 0 || blocks > 65535) return SQP_ERR_SHAPE;
     const size_t n = bytes / 16;
-    if (nt) read_probe_kernel<true><<<4096, 256, 0, (hipStream_t)stream>>>((const probe_u32x4 *)src, n, (uint32_t *)sink);
-    else read_probe_kernel<false><<<4096, 256, 0, (hipStream_t)stream>>>((const probe_u32x4 *)src, n, (uint32_t *)sink);
+    if (nt) read_probe_kernel<true><<<blocks, 256, 0, (hipStream_t)stream>>>((const probe_u32x4 *)src, n, (uint32_t *)sink);
+    else read_probe_kernel<false><<<blocks, 256, 0, (hipStream_t)stream>>>((const probe_u32x4 *)src, n, (uint32_t *)sink);
     return sqp_launch_status();
 }
 

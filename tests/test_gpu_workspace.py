@@ -141,7 +141,7 @@ def test_workspace_graph_capture_side_stream(orc, sqp):
         ws.check("workspace")
     finally:
         torch.cuda.synchronize()
-        L.sqp_set_workspace(None, ctypes.c_size_t(0), None)
+        sqp.set_workspace(0)   # through the binding, so that it knows no workspace is set any more
 
 
 def test_workspace_too_small_or_absent(orc, sqp):
@@ -179,7 +179,7 @@ def test_workspace_too_small_or_absent(orc, sqp):
         assert L.sqp_set_workspace(ws.ptr, ctypes.c_size_t(TICKET_BYTES), None) == -6
     finally:
         torch.cuda.synchronize()
-        L.sqp_set_workspace(None, ctypes.c_size_t(0), None)
+        sqp.set_workspace(0)   # through the binding, so that it knows no workspace is set any more
 
 
 @pytest.mark.parametrize("M,K,N,group", [
@@ -217,7 +217,7 @@ def test_gemm_outputs_between_guards(orc, sqp, M, K, N, group, with_ws):
                 ws.check("workspace after silu_mul")
     finally:
         torch.cuda.synchronize()
-        L.sqp_set_workspace(None, ctypes.c_size_t(0), None)
+        sqp.set_workspace(0)   # through the binding, so that it knows no workspace is set any more
 
 
 @pytest.mark.parametrize("K,N,group", [(256, 8, 128), (384, 72, 64), (1024, 520, 128), (96, 24, 24), (512, 136, 32), (2048, 1000, 256)])

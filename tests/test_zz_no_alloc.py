@@ -56,7 +56,7 @@ def _both(L, sqp, M, K, N, g, dx, dp, dsc, dz):
         assert rc == 0, rc
         torch.cuda.synchronize()
     finally:
-        L.sqp_set_workspace(None, ctypes.c_size_t(0), None)
+        sqp.set_workspace(0)   # through the binding, so that it knows no workspace is set any more
     return y_s.cpu().numpy(), y_w.cpu().numpy()
 
 
