@@ -15,7 +15,8 @@
 //     the tile is transposed on its way into LDS (8 rows x 2 columns per thread, v_perm_b32).
 //   - Packed words are loaded straight into registers (a word is one lane's B operand) and
 //     unpacked with the step negated.
-// This is an offline calibration kernel: plain loads and barriers, no hand pipelining.
+// This is an offline calibration kernel: plain loads and barriers; the only pipelining is that
+// the global loads of the next k-step are issued before the current one is multiplied.
 #include "sqp_common.h"
 #include "sqp_w4_unpack.h"
 
@@ -54,31 +55,56 @@ quant_loss_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, con
     const int wkb = tid >> 6, wcp = tid & 63;                  // W: k-block of 8 rows, column pair
     const int wcol = n0 + 2 * wcp;
 
-    for (int k0 = 0; k0 < K; k0 += LBK) {
-        // ---- global -> LDS (K is a multiple of 8, so a group of 8 halves is in or out as a whole)
+    // Software pipeline over the k-steps: the global loads of step k0 + LBK are in flight (into
+    // registers) while step k0 is multiplied out of LDS.
+    uint4 rx[2], rh[2];     // X and X_hat: this thread's 2 x 8 halves of its row
+    uint32_t rw[8];         // W: 8 rows x one column pair
+    uint32_t rword[2][2], rz[2][2], rd[2][2];  // packed word, zero point, negated step per (k sub-step, column tile)
+    auto fetch = [&](int k0) {
 #pragma unroll
         for (int j = 0; j < 2; j++) {
             const int kk = k0 + apart * 16 + j * 8;
-            uint4 vx = make_uint4(0, 0, 0, 0), vh = vx;
+            rx[j] = make_uint4(0, 0, 0, 0);
+            rh[j] = rx[j];
             if (kk < K) {
-                vx = *reinterpret_cast<const uint4 *>(x + (size_t)agrow * K + kk);
-                vh = *reinterpret_cast<const uint4 *>(xh + (size_t)agrow * K + kk);
+                rx[j] = *reinterpret_cast<const uint4 *>(x + (size_t)agrow * K + kk);
+                rh[j] = *reinterpret_cast<const uint4 *>(xh + (size_t)agrow * K + kk);
             }
-            *reinterpret_cast<uint4 *>(&sx[arow][apart * 16 + j * 8]) = vx;
-            *reinterpret_cast<uint4 *>(&sxh[arow][apart * 16 + j * 8]) = vh;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const int kk = k0 + wkb * 8 + i;
+            rw[i] = (kk < K && wcol < N) ? *reinterpret_cast<const uint32_t *>(w + (size_t)kk * N + wcol) : 0u;
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ks++)
+#pragma unroll
+            for (int t = 0; t < 2; t++) {
+                const int kk = k0 + ks * 16 + kb * 8;
+                const int col = n0 + wn * 64 + t * 32 + l32;
+                rword[ks][t] = 0; rz[ks][t] = 0; rd[ks][t] = 0;
+                if (kk < K && col < N) {
+                    const size_t gi = (size_t)(kk / group) * N + col;
+                    rword[ks][t] = packed[(size_t)(kk >> 3) * N + col];
+                    rz[ks][t] = zeros[gi];
+                    rd[ks][t] = __builtin_bit_cast(uint16_t, scales[gi]) ^ 0x8000u;  // -Delta
+                }
+            }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < K; k0 += LBK) {
+        // ---- registers -> LDS (K is a multiple of 8, so a group of 8 halves is in or out as a whole)
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            *reinterpret_cast<uint4 *>(&sx[arow][apart * 16 + j * 8]) = rx[j];
+            *reinterpret_cast<uint4 *>(&sxh[arow][apart * 16 + j * 8]) = rh[j];
         }
         {
-            uint32_t v[8];
-#pragma unroll
-            for (int i = 0; i < 8; i++) {
-                const int kk = k0 + wkb * 8 + i;
-                v[i] = (kk < K && wcol < N) ? *reinterpret_cast<const uint32_t *>(w + (size_t)kk * N + wcol) : 0u;
-            }
             uint4 c0, c1;  // column wcol: the low halves of the 8 rows; column wcol + 1: the high halves
-            c0.x = __builtin_amdgcn_perm(v[1], v[0], 0x05040100u); c1.x = __builtin_amdgcn_perm(v[1], v[0], 0x07060302u);
-            c0.y = __builtin_amdgcn_perm(v[3], v[2], 0x05040100u); c1.y = __builtin_amdgcn_perm(v[3], v[2], 0x07060302u);
-            c0.z = __builtin_amdgcn_perm(v[5], v[4], 0x05040100u); c1.z = __builtin_amdgcn_perm(v[5], v[4], 0x07060302u);
-            c0.w = __builtin_amdgcn_perm(v[7], v[6], 0x05040100u); c1.w = __builtin_amdgcn_perm(v[7], v[6], 0x07060302u);
+            c0.x = __builtin_amdgcn_perm(rw[1], rw[0], 0x05040100u); c1.x = __builtin_amdgcn_perm(rw[1], rw[0], 0x07060302u);
+            c0.y = __builtin_amdgcn_perm(rw[3], rw[2], 0x05040100u); c1.y = __builtin_amdgcn_perm(rw[3], rw[2], 0x07060302u);
+            c0.z = __builtin_amdgcn_perm(rw[5], rw[4], 0x05040100u); c1.z = __builtin_amdgcn_perm(rw[5], rw[4], 0x07060302u);
+            c0.w = __builtin_amdgcn_perm(rw[7], rw[6], 0x05040100u); c1.w = __builtin_amdgcn_perm(rw[7], rw[6], 0x07060302u);
             *reinterpret_cast<uint4 *>(&sw[2 * wcp][wkb * 8]) = c0;
             *reinterpret_cast<uint4 *>(&sw[2 * wcp + 1][wkb * 8]) = c1;
         }
@@ -87,19 +113,11 @@ quant_loss_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, con
 #pragma unroll
         for (int ks = 0; ks < 2; ks++)
 #pragma unroll
-            for (int t = 0; t < 2; t++) {
-                const int kk = k0 + ks * 16 + kb * 8;
-                const int col = n0 + wn * 64 + t * 32 + l32;
-                uint32_t word = 0, z = 0, d = 0;
-                if (kk < K && col < N) {
-                    const size_t gi = (size_t)(kk / group) * N + col;
-                    word = packed[(size_t)(kk >> 3) * N + col];
-                    z = zeros[gi];
-                    d = __builtin_bit_cast(uint16_t, scales[gi]) ^ 0x8000u;  // -Delta
-                }
-                bq[ks][t] = dequant_word_scaled(word, neg_hi_of(z), neg_lo_of(z), __builtin_bit_cast(h16x2, d * 0x00010001u), uc);
-            }
+            for (int t = 0; t < 2; t++)
+                bq[ks][t] = dequant_word_scaled(rword[ks][t], neg_hi_of(rz[ks][t]), neg_lo_of(rz[ks][t]),
+                                                __builtin_bit_cast(h16x2, rd[ks][t] * 0x00010001u), uc);
         __syncthreads();
+        if (k0 + LBK < K) fetch(k0 + LBK);
 #pragma unroll
         for (int ks = 0; ks < 2; ks++) {
             h16x8 ax[2], ah[2], bw[2];

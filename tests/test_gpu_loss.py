@@ -86,3 +86,33 @@ def test_alpha_search_matches_oracle(orc, sqp):
     assert ref[i_best] <= min(ref) * (1 + 2 * LOSS_RTOL)
     # smoothing must pay off on this workload: the best loss is well below the alpha = 0 loss
     assert min(ref) < 0.8 * ref[0]
+
+
+def test_alpha_search_equals_single_calls(orc, sqp):
+    """The one-call search (per-channel maxima computed once) gives, bit for bit, the losses
+    that the chain of single entry points gives for each alpha, and the index of the first
+    smallest one; argument errors are reported before anything is enqueued."""
+    import ctypes
+    T, K, N, g = 70, 512, 264, 64
+    _, xcal, w = wl.layer_inputs(1, K, N)
+    dx, dw = dev(np.ascontiguousarray(xcal[:T])), dev(w)
+    alphas = [0.4, 0.0, 1.0, 0.25, 0.4]
+    best, curve = sqp.alpha_search(dx, dw, g, alphas)
+    singles = []
+    for a in alphas:
+        s = sqp.smooth_scales(dx, dw, a)
+        q = sqp.quantize_pack(sqp.smooth_apply_w(dw, s), g)
+        singles.append(float(host(sqp.quant_loss(dx, dw, sqp.smooth_apply_x(dx, s), q[0], q[1], q[2], g))[0]))
+    assert [v for _, v in curve] == singles
+    assert best == alphas[int(np.argmin(singles))]
+    assert curve[0][1] == curve[4][1]                          # the same alpha twice: the same bits
+    L = sqp.lib()
+    good = ctypes.c_void_p(0x1000)
+    bad_alpha = (ctypes.c_float * 2)(0.5, 1.5)
+    assert L.sqp_alpha_search(T, N, K, g, 2, bad_alpha, *([good] * 13)) == -4
+    ok_alpha = (ctypes.c_float * 2)(0.5, 0.25)
+    assert L.sqp_alpha_search(T, N, K, g, 0, ok_alpha, *([good] * 13)) == -2
+    assert L.sqp_alpha_search(T, N, K, 100, 2, ok_alpha, *([good] * 13)) == -2
+    # `best` missing (the last pointer before the stream): rejected before anything is enqueued.
+    # Every call above and this one must fail validation: the pointers are not real.
+    assert L.sqp_alpha_search(T, N, K, g, 2, ok_alpha, *([good] * 11), None, None) == -1
