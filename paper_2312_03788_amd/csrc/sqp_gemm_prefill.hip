@@ -1,17 +1,18 @@
 // Tiled matrix-core W4A16 GEMM for large M (prefill): y = x * w_hat, Eq. 3 of
 // arXiv 2312.03788 with w_hat = fp16((code - Z) * Delta) of Eq. 1, group-wise along K.
 //
-// A workgroup of W = 4 waves (one per SIMD, the whole register file each) computes a
-// 256 x 256 tile of y; wave (wm, wn) owns 128 rows x 128 columns of it as 4 x 4 accumulator
-// tiles of v_mfma_f32_32x32x16_f16 (256 fp32 registers per lane).
+// A workgroup of 4 waves (one per SIMD, the whole register file each) computes a 128 x 512
+// tile of y, the waves side by side on the same 128 rows (or a 256 x 256 tile, waves 2 x 2);
+// a wave owns 128 rows x 128 columns as 4 x 4 accumulator tiles of v_mfma_f32_32x32x16_f16
+// (256 fp32 registers per lane).
 //   - Weights never pass through LDS: one dwordx4 load per lane fetches, for k-block
 //     (lane / 32), the packed words of 4 adjacent columns; a word is 8 consecutive k of one
 //     column, i.e. one lane's B operand of the 32x32x16 MFMA (column = lane % 32).  The word
 //     is unpacked in registers to the fp16 dequantised weights (13 VALU ops) and each B
 //     operand feeds 4 MFMAs (the 4 row tiles); each activation fragment feeds 4 as well
 //     (4.25 VALU ops per MFMA).
-//   - Activations are the shared operand: a 256 x 64 slice of x per stage is copied once per
-//     workgroup straight into a four-slot LDS ring (direct global->LDS loads of whole
+//   - Activations are the shared operand: a 128 x 64 (256 x 64) slice of x per stage is copied
+//     once per workgroup straight into a four-slot LDS ring (direct global->LDS loads of whole
 //     128-byte lines, pieces XOR-swizzled so that the 16-byte reads of one k-step spread over
 //     all banks) and every wave reads its A operands from there.
 //   - With a single wave per SIMD the order of issue is the schedule, so the MFMAs and the
@@ -21,9 +22,9 @@
 //     its loads, barrier) sits inside the last k-step, so the pipeline never drains.
 //   - Loads, waits and the per-stage barrier are explicit (assembly), as in the decode
 //     kernel: two stages stay in flight while one is consumed.
-// The same kernel with W = 8 waves of 128 x 64 (two per SIMD) needs fewer cycles per MFMA but
-// the chip then clocks lower under its power limit and the result was a little slower, so the
-// four-wave shape is the one launched.
+// Eight waves of 128 x 64 (two per SIMD) needed fewer cycles per MFMA, but the chip then
+// clocked lower under its power limit and the result was a little slower, so one wave per SIMD
+// it is.
 #include <type_traits>
 
 #include "sqp_common.h"
