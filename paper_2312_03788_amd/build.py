@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsqp.so")
 
-SOURCES = ["sqp_api.hip", "sqp_companion.hip", "sqp_gemm_decode.hip", "sqp_gemm_prefill.hip", "sqp_loss.hip", "sqp_mlp.hip", "sqp_static.hip"]
+SOURCES = ["sqp_api.hip", "sqp_companion.hip", "sqp_gemm_decode.hip", "sqp_gemm_prefill.hip", "sqp_gemm_slice.hip", "sqp_loss.hip", "sqp_mlp.hip", "sqp_static.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-I" + os.path.join(ROOT, "include"),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
@@ -26,6 +26,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
 #                  must come after the kernel's last barrier, i.e. after the main loop and its
 #                  final wait for all outstanding loads (checked in the generated assembly).
 GUARDED_KERNELS = {"sqp_gemm_decode.hip": ("w4a16_decode_kernel", "none"),
+                   "sqp_gemm_slice.hip": ("w4a16_decode_slice_kernel", "none"),
                    "sqp_gemm_prefill.hip": ("w4a16_prefill_kernel", "after-last-barrier")}
 
 

@@ -58,6 +58,10 @@ int sqp_gemm_decode(int M, int N, int K, int group, const h16 *x, const uint32_t
                     const h16 *scales, const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t stream);
 int sqp_gemm_prefill(int M, int N, int K, int group, const h16 *x, const uint32_t *packed,
                      const h16 *scales, const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t stream);
+// Column-slice variant of the decode path (up to 16 rows, groups of 128; needs no workspace).
+bool sqp_gemm_slice_covers(int M, int N, int K, int group);
+int sqp_gemm_slice(int variant, int M, int N, int K, const h16 *x, const uint32_t *packed, const h16 *scales,
+                   const uint8_t *zeros, h16 *y, int epi, hipStream_t stream);
 // Shared by every GEMM entry point: argument checks and the choice between the two paths.
 int sqp_gemm_entry(int M, int N, int K, int group, const void *x, const uint32_t *packed, const void *scales,
                    const uint8_t *zeros, void *y, int epi, const SqpWorkspace &ws, void *stream);

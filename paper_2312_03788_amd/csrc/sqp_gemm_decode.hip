@@ -90,7 +90,11 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     constexpr int WAVES = NW * KW;
     constexpr int KS = KSPG / KW;                // k-steps of a chunk this wave takes
     static_assert(KS * KW == KSPG, "k-steps divide among a strip's waves");
-    constexpr int OX = (XBLOCKS + WAVES - 1) / WAVES;  // direct loads per wave per chunk
+    constexpr int OX = (XBLOCKS + WAVES - 1) / WAVES;  // direct loads per wave per chunk (at most)
+    // When the blocks do not divide evenly among the waves, waves XREM and above copy one block
+    // fewer (none, where a chunk has fewer blocks than the workgroup has waves): every block is
+    // fetched exactly once per workgroup, and such a wave waits on a count of its own.
+    constexpr int XREM = XBLOCKS % WAVES;
     constexpr int OW = KS + 2;                   // weight-side loads per wave per chunk
     // With four row tiles the per-chunk scaling of 64 accumulator registers costs more vector
     // work than multiplying the unpacked weights by the step (4 packed multiplies per word, as
@@ -202,8 +206,10 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     };
     // wait until at most `after` loads are outstanding, then tie the stage's registers to the
     // wait so that no use of them is scheduled ahead of it
-    auto landed = [&](Stage &s, auto after) {
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(after)::value) : "memory");
+    const bool x_full = XREM == 0 || wv < XREM;  // wave-uniform: this wave issues all OX direct loads per chunk
+    auto landed = [&](Stage &s) {
+        if (x_full) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((P - 1) * (OX + OW)) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((P - 1) * (OX - 1 + OW)) : "memory");
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) asm volatile("" : "+v"(s.w[ks]));
         asm volatile("" : "+v"(s.sc));
@@ -227,6 +233,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     auto issue_x = [&](int slot) {
 #pragma unroll
         for (int i = 0; i < OX; i++) {
+            if (i + 1 == OX && !x_full) break;
             const int b = (wv + i * WAVES) % XBLOCKS;
             const unsigned char *src = xq + xoff[i];
             unsigned char *dst = xring + slot * XSTAGE + b * 1024;
@@ -350,9 +357,10 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // The loading side of the loop body is free of branches: the chunk count is rounded up to a
     // multiple of D; loads past the range point at the range's last chunk (the activations: cache
     // hits) or are issued with an empty execution mask (the weight side); the arithmetic of such
-    // padded iterations is skipped.  Every iteration thus issues the same OX + OW loads, and
-    // since loads complete in issue order "at most (P-1)(OX + OW) loads outstanding" means all
-    // but the last P-1 iterations' have landed.  Past the range the pointers stop.
+    // padded iterations is skipped.  Every iteration of a wave thus issues the same number of
+    // loads (OX + OW, or one fewer on the waves that copy one block less), and since loads
+    // complete in issue order "at most P-1 iterations' worth of loads outstanding" means all but
+    // the last P-1 iterations' have landed.  Past the range the pointers stop.
     const int glast = g1 > g0 ? g1 - 1 : g0;
     auto advance = [&]() {
         const bool more = gi < glast;
@@ -379,7 +387,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 #pragma unroll
         for (int d = 0; d < D; d++) {
             const int gg = g + d;
-            landed(st[d], std::integral_constant<int, (P - 1) * (OX + OW)>());
+            landed(st[d]);
             asm volatile("s_barrier" ::: "memory");
             const int fill = slot >= 1 ? slot - 1 : XD - 1;  // (slot + P) % XD
             issue_x(fill);
@@ -664,6 +672,26 @@ static Plan g_force_plan = {0, 0};
 extern "C" void sqp_debug_set_decode_split(int split) { g_force_split = split; }
 extern "C" void sqp_debug_set_decode_plan(int nw, int split) { g_force_plan = Plan{nw, split}; }
 extern "C" void sqp_debug_set_decode_kw(int kw) { g_decode_kw = kw; }
+static int g_slice_mode = 0;
+extern "C" void sqp_debug_set_decode_slice(int mode) { g_slice_mode = mode; }
+
+// Whether a call takes the column-slice kernel (-1: no), and which variant (0: 32-column
+// slices, 1: 64-column slices).  From sweeps on Code Llama shapes: the slice kernel has no
+// hand-over between workgroups, but every workgroup fetches all of x from L2, and that traffic
+// (workgroups x rows x K) is what it costs.  It wins up to 8 rows (a third to a half of the
+// activation traffic of 16 rows): 64-column slices from 150 slices on; below that 32-column
+// slices, unless K is long and the slices are few (then the activations dominate again).
+static int slice_variant(int M, int N, int K, int group)
+{
+    if (g_slice_mode < 0 || !sqp_gemm_slice_covers(M, N, K, group)) return -1;
+    if (g_slice_mode > 0) return g_slice_mode - 1;
+    if (M > 8) return -1;
+    const int slices64 = (N + 63) / 64, slices32 = (N + 31) / 32;
+    if (slices64 >= 150) return 1;
+    if (slices32 >= 96 && (slices32 >= 200 || K <= 8192)) return 0;
+    return -1;
+}
+extern "C" int sqp_debug_decode_slice_choice(int M, int N, int K, int group) { return slice_variant(M, N, K, group); }
 
 int sqp_gemm_generic(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
                      const uint8_t *zeros, h16 *y, hipStream_t stream)
@@ -701,6 +729,7 @@ size_t sqp_gemm_decode_partial_bytes(int M, int N, int K, int group)
 {
     const int kspg = group == 32 ? 1 : (group == 64 ? 2 : (group % 128 == 0 ? 4 : 0));
     if (kspg == 0) return 0;  // generic kernel
+    if (slice_variant(M, N, K, group) >= 0) return 0;
     const Plan p = plan_for(M, N, K, group, true);
     const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
     int nw = p.nw;
@@ -713,6 +742,8 @@ size_t sqp_gemm_decode_partial_bytes(int M, int N, int K, int group)
 int sqp_gemm_decode(int M, int N, int K, int group, const h16 *x, const uint32_t *packed, const h16 *scales,
                     const uint8_t *zeros, h16 *y, int epi, const SqpWorkspace &ws, hipStream_t stream)
 {
+    const int sv = slice_variant(M, N, K, group);
+    if (sv >= 0) return sqp_gemm_slice(sv, M, N, K, x, packed, scales, zeros, y, epi, stream);
     const Plan p = plan_for(M, N, K, group, ws.partial != nullptr);
     if (group == 32) return dispatch_kspg<1>(p, M, N, K, 1, x, packed, scales, zeros, y, epi, ws, stream);
     if (group == 64) return dispatch_kspg<2>(p, M, N, K, 1, x, packed, scales, zeros, y, epi, ws, stream);

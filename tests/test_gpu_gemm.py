@@ -261,6 +261,49 @@ def test_decode_other_strip_counts(orc, sqp, M, K, N, group, nw, split):
         L.sqp_debug_set_decode_plan(0, 0)
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("M,K,N", [
+    (1, 128, 8), (3, 256, 40), (5, 1152, 72), (16, 384, 520), (7, 1024, 1032), (16, 1536, 2056), (9, 128 * 7, 200),
+    (16, 4096, 1024), (2, 128 * 19, 264)])
+def test_decode_slice_kernel(orc, sqp, M, K, N, mode):
+    """The column-slice kernel (a workgroup owns 32 columns over all of K, its waves take every
+    WV-th chunk and add up through LDS), both variants, forced through the hook: fewer chunks
+    than waves, chunk counts that do not divide among the waves, ragged column counts; repeated
+    runs are bit-identical."""
+    print("case slice", M, K, N, mode, flush=True)
+    xs, p, sc, z = _layer(orc, M, K, N, 128)
+    L = sqp.lib()
+    L.sqp_debug_set_decode_slice(mode)
+    try:
+        y0 = _check(orc, sqp, xs, p, sc, z, 128)
+        y1 = _check(orc, sqp, xs, p, sc, z, 128)
+        assert np.array_equal(y0.view(np.uint16), y1.view(np.uint16))
+    finally:
+        L.sqp_debug_set_decode_slice(0)
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+def test_decode_slice_integer_exact(orc, sqp, mode):
+    """Integer operands (step 1, Z = 0): every partial sum is an exact integer in fp32, so the
+    slice kernel's result is the integer product rounded once to fp16."""
+    rng = np.random.Generator(np.random.PCG64(5))
+    M, N, K, g = 16, 104, 128 * 11, 128
+    q = rng.integers(0, 16, size=(K, N))
+    x = rng.integers(-4, 5, size=(M, K))
+    p = np.zeros((K // 8, N), np.uint32)
+    for i in range(8):
+        p |= q[i::8].astype(np.uint32) << np.uint32(4 * i)
+    ones = np.ones((K // g, N), np.float16)
+    zz = np.zeros((K // g, N), np.uint8)
+    L = sqp.lib()
+    L.sqp_debug_set_decode_slice(mode)
+    try:
+        y = host(sqp.w4a16_gemm(dev(x.astype(np.float16)), dev(p), dev(ones), dev(zz), g))
+    finally:
+        L.sqp_debug_set_decode_slice(0)
+    assert np.array_equal(y, (x @ q).astype(np.float16))
+
+
 @pytest.mark.parametrize("M,K,N,group", _random_shapes(202, 8, 65, 700))
 def test_prefill_random_shapes(orc, sqp, M, K, N, group):
     """Random shapes above 64 rows (tiled kernel: wide and narrow tiles, K parts; groups of 32

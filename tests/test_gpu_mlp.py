@@ -93,6 +93,32 @@ def test_gemm_silu_mul(orc, sqp, M, K, N, group, ksplit):
     assert np.abs(y_ref[:, 0::2]).max() > 1.0              # the gate really leaves the linear range
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("M,K,N", [(4, 1024, 1024), (16, 640, 272), (9, 2048, 80)])
+def test_gemm_silu_mul_slice_kernel(orc, sqp, M, K, N, mode):
+    """The fused activation through the column-slice kernel (a lane's two columns are one
+    (gate, up) pair)."""
+    print("case silu slice", M, K, N, mode, flush=True)
+    group = 128
+    x, xcal, _ = wl.layer_inputs(M, K, 8)
+    wg, wu = wl.weight(K, N // 2, seed=41), wl.weight(K, N // 2, seed=42)
+    w = orc.interleave_gate_up(wg, wu)
+    s = orc.smooth_scales(xcal, w, wl.ALPHA)
+    xs = orc.smooth_apply_x(x * np.float16(0.25), s)
+    p, sc, z = orc.quantize_pack(orc.smooth_apply_w((w.astype(np.float32) * 8).astype(np.float16), s), group)
+    y_ref, t_ref = orc.w4a16_gemm_ref(xs, p, sc, z, group)
+    h_ref, tol = _silu_tolerance(orc, y_ref, t_ref)
+    L = sqp.lib()
+    L.sqp_debug_set_decode_slice(mode)
+    try:
+        h = host(sqp.w4a16_gemm_silu_mul(dev(xs), dev(p), dev(sc), dev(z), group)).astype(np.float64)
+    finally:
+        L.sqp_debug_set_decode_slice(0)
+    assert h.shape == (M, N // 2)
+    err = np.abs(h - h_ref)
+    assert np.all(err <= tol), "worst err/tol %.3f" % float((err / tol).max())
+
+
 def test_mlp_block_end_to_end(orc, sqp):
     """The folded, quantised block on the GPU (RMSNorm with gamma / s1 -> fused gate/up GEMM ->
     down GEMM) against the same pipeline evaluated by the oracle stage by stage, and its error
