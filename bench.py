@@ -253,19 +253,33 @@ def side_measurements(torch, sqp, wl, dev, shapes, layers, s_first, activation, 
         b = wl.algorithmic_bytes(M_decode, N, K, G)
         by_shape["%dx%d" % (K, N)] = {"us": round(t * 1e6, 2), "gbs": round(b / t / 1e9, 1), "pct_hbm_peak": round(100 * b / t / 1e9 / HBM_PEAK_GBS, 1)}
     extra["decode_m%d_by_shape" % M_decode] = by_shape
-    # decode at M=1 over all resident layers
-    M = 1
-    xs = [sqp.smooth_apply_x(activation(M, K, 2000 + M), s_first[si]) for si, (K, N) in enumerate(shapes)]
-    ys = [torch.empty((M, N), device=dev, dtype=torch.float16) for (K, N) in shapes]
+    # decode with fewer rows (up to 8 rows take the column-slice kernel) over all resident layers,
+    # and by layer shape at M = 1
+    for M in (1, 8):
+        xs = [sqp.smooth_apply_x(activation(M, K, 2000 + M), s_first[si]) for si, (K, N) in enumerate(shapes)]
+        ys = [torch.empty((M, N), device=dev, dtype=torch.float16) for (K, N) in shapes]
 
-    def sweep():
-        for per in layers:
-            for si, (p, sc, z) in enumerate(per):
-                sqp.w4a16_gemm(xs[si], p, sc, z, G, out=ys[si])
-    t = _graph_time(torch, sweep, 3)
-    b = len(layers) * sum(wl.algorithmic_bytes(M, N, K, G) for (K, N) in shapes)
-    extra["decode_m1_gbs"] = round(b / t / 1e9, 1)
-    extra["decode_m1_pct_hbm_peak"] = round(100 * b / t / 1e9 / HBM_PEAK_GBS, 2)
+        def sweep():
+            for per in layers:
+                for si, (p, sc, z) in enumerate(per):
+                    sqp.w4a16_gemm(xs[si], p, sc, z, G, out=ys[si])
+        t = _graph_time(torch, sweep, 3)
+        b = len(layers) * sum(wl.algorithmic_bytes(M, N, K, G) for (K, N) in shapes)
+        extra["decode_m%d_gbs" % M] = round(b / t / 1e9, 1)
+        extra["decode_m%d_pct_hbm_peak" % M] = round(100 * b / t / 1e9 / HBM_PEAK_GBS, 2)
+        if M == 1:
+            by_shape = {}
+            for si, (K, N) in enumerate(shapes):
+                def sweep_one():
+                    for per in layers:
+                        p, sc, z = per[si]
+                        sqp.w4a16_gemm(xs[si], p, sc, z, G, out=ys[si])
+                t1 = _graph_time(torch, sweep_one, 5) / len(layers)
+                b1 = wl.algorithmic_bytes(M, N, K, G)
+                by_shape["%dx%d" % (K, N)] = {"us": round(t1 * 1e6, 2), "gbs": round(b1 / t1 / 1e9, 1),
+                                              "pct_hbm_peak": round(100 * b1 / t1 / 1e9 / HBM_PEAK_GBS, 1),
+                                              "kernel": ("strips", "slices of 32 columns", "slices of 64 columns")[1 + L.sqp_debug_decode_slice_choice(M, N, K, G)]}
+            extra["decode_m1_by_shape"] = by_shape
     # the tiled path at M = 2048 and 4096, the four shapes, rotating over resident layers; the
     # average launch duration comes from HIP events around the timed launches
     roofline_prefill = None
