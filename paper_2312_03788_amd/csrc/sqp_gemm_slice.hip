@@ -10,8 +10,8 @@
 // its own, so there is no barrier) and add their fp32 sums through LDS at the end, in wave
 // order: no workspace, no tickets, and the result does not depend on scheduling.
 // The price: every workgroup fetches all of x (from L2), workgroups x rows x K x 2 bytes per
-// launch, which at 16 rows costs as much as the hand-over saved; the kernel is used up to 8
-// rows, where only the blocks of four rows that hold real rows are fetched.
+// launch, which at 16 rows costs as much as the hand-over saved; the kernel is used up to 8 or
+// 12 rows, where only the blocks of four rows that hold real rows are fetched.
 //
 // Column mapping: lane (lc = lane % 16, lk = lane / 16) holds the TB adjacent columns
 // n0 + TB lc ... (one 8- or 16-byte load per k-step: their packed words, k-block lk), which are
@@ -301,14 +301,16 @@ int sqp_gemm_slice(int variant, int M, int N, int K, const h16 *x, const uint32_
 {
 #define SQP_SLICE_LAUNCH(TB, XB) \
     w4a16_decode_slice_kernel<TB, 8, 2, XB><<<(N + 16 * TB - 1) / (16 * TB), 8 * 64, 0, stream>>>(M, N, K, x, packed, scales, zeros, y, epi)
-    const int xb = M <= 4 ? 1 : (M <= 8 ? 2 : 4);
+    const int xb = (M + 3) / 4;  // blocks of four rows that hold real rows
     if (variant == 0) {
         if (xb == 1) SQP_SLICE_LAUNCH(2, 1);
         else if (xb == 2) SQP_SLICE_LAUNCH(2, 2);
+        else if (xb == 3) SQP_SLICE_LAUNCH(2, 3);
         else SQP_SLICE_LAUNCH(2, 4);
     } else {
         if (xb == 1) SQP_SLICE_LAUNCH(4, 1);
         else if (xb == 2) SQP_SLICE_LAUNCH(4, 2);
+        else if (xb == 3) SQP_SLICE_LAUNCH(4, 3);
         else SQP_SLICE_LAUNCH(4, 4);
     }
 #undef SQP_SLICE_LAUNCH

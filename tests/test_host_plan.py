@@ -60,17 +60,21 @@ def test_decode_plan_34b_values(L):
 
 
 def test_decode_slice_choice(L):
-    """Which calls take the column-slice kernel: up to 8 rows and groups of 128 only; 64-column
+    """Which calls take the column-slice kernel: groups of 128 only; up to 8 rows, 64-column
     slices on the wide layers, 32-column slices on the narrow ones unless K is long and the
-    slices are few; the 16-row calls of the benchmark sweep keep the strip kernel."""
+    slices are few; 9 to 12 rows only where the layer is not too wide and K not long; the 16-row
+    calls of the benchmark sweep keep the strip kernel."""
     L.sqp_debug_decode_slice_choice.restype = ctypes.c_int
     ch = lambda M, K, N, g=128: L.sqp_debug_decode_slice_choice(M, N, K, g)
     assert [ch(1, K, N) for (K, N) in wl.MODEL_SHAPES["34b"]] == [1, 0, 1, 0]
     assert [ch(8, K, N) for (K, N) in wl.MODEL_SHAPES["34b"]] == [1, 0, 1, 0]
     assert [ch(1, K, N) for (K, N) in wl.MODEL_SHAPES["13b"]] == [1, 0, 1, -1]
     assert [ch(4, K, N) for (K, N) in wl.MODEL_SHAPES["7b"]] == [1, 0, 1, -1]
+    assert [ch(12, K, N) for (K, N) in wl.MODEL_SHAPES["34b"]] == [1, 0, -1, -1]
+    assert [ch(9, K, N) for (K, N) in wl.MODEL_SHAPES["13b"]] == [1, 0, -1, -1]
+    assert [ch(12, K, N) for (K, N) in wl.MODEL_SHAPES["7b"]] == [1, 0, 1, -1]
     for (K, N) in wl.MODEL_SHAPES["34b"]:
-        assert ch(9, K, N) == -1 and ch(16, K, N) == -1 and ch(64, K, N) == -1
+        assert ch(13, K, N) == -1 and ch(16, K, N) == -1 and ch(64, K, N) == -1
         assert ch(1, K, N, 64) == -1 and ch(1, K, N, 256) == -1
     assert ch(1, 4096, 1024) == -1 and ch(1, 128, 8) == -1      # few slices: the strip kernel and its K split
 
