@@ -34,7 +34,8 @@ def _oracle_chain(orc, xcal, w, alpha, group):
 
 @pytest.mark.parametrize("M,K,N,group,alpha", [
     (4, 1024, 1024, 128, 0.5), (37, 264, 72, 24, 0.25), (130, 512, 136, 64, 0.85), (129, 40, 8, 8, 0.5),
-    (512, 2048, 520, 128, 0.5), (300, 1024, 1000, 256, 0.0)])
+    (512, 2048, 520, 128, 0.5), (300, 1024, 1000, 256, 0.0),
+    (256, 1024, 384, 128, 0.5), (128, 192, 128, 32, 0.3)])  # the last two: whole tiles only (the variant without bounds checks)
 def test_quant_loss_parity(orc, sqp, M, K, N, group, alpha):
     print("case loss", M, K, N, group, alpha, flush=True)
     _, xcal, w = wl.layer_inputs(1, K, N)
