@@ -19,6 +19,7 @@ void sqp_debug_set_decode_max_m(int m);            /* rows up to which that path
 void sqp_debug_set_decode_split(int split);        /* force the number of K parts; 0 = automatic */
 void sqp_debug_set_decode_plan(int nw, int split); /* force strips per workgroup and K parts; (0, 0) = automatic */
 void sqp_debug_set_decode_kw(int kw);              /* 1 = never two waves per strip; 0 = automatic */
+void sqp_debug_set_decode_kp(int kp);              /* two chunks per iteration (twice the waves): 0 = automatic, 1 = never, 2 = wherever built */
 void sqp_debug_set_decode_slice(int mode);         /* column-slice kernel (M <= 16, groups of 128): 0 = automatic, -1 = never,
                                                       1 = always with 32-column slices, 2 = always with 64-column slices */
 /* Which kernel a call would take: -1 = the strip kernel below, 0 / 1 = the column-slice kernel

@@ -66,12 +66,15 @@ constexpr int TICKET_STRIDE = 32;
 // MT: 16-row tiles of x (M <= 16*MT).  NW: 64-column strips per workgroup.
 // KSPG: k-steps (of 32) per chunk; a quantisation group is cpg chunks (cpg = 1 unless the
 // group is a multiple of 128 above 128).
-// KW: waves per strip.  With KW = 2 a strip's two waves share every chunk, each taking half of
-// its k-steps, and add their sums through LDS at the end: two waves per SIMD, whose
+// KW: waves per strip and chunk.  With KW = 2 a strip's two waves share every chunk, each taking
+// half of its k-steps, and add their sums through LDS at the end: two waves per SIMD, whose
 // instructions the hardware interleaves, where a launch has only one workgroup per compute
 // unit and a single wave's dependent vector instructions would leave issue slots empty.
-template <int MT, int NW, int KSPG, int KW>
-__global__ void __launch_bounds__(NW * KW * 64) __attribute__((amdgpu_waves_per_eu(KW == 2 ? 2 : (MT == 1 && NW >= 4 ? 3 : 1))))
+// KP: chunks per iteration.  With KP = 2 the workgroup has twice the waves and takes two
+// consecutive chunks per iteration, one per half of its waves (same purpose as KW = 2, without
+// making a wave's share of a chunk smaller); the halves add up through LDS like KW's.
+template <int MT, int NW, int KSPG, int KW, int KP>
+__global__ void __launch_bounds__(NW * KW * KP * 64) __attribute__((amdgpu_waves_per_eu(KW * KP >= 2 ? 2 : (MT == 1 && NW >= 4 ? 3 : 1))))
 w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, const uint32_t *__restrict__ packed,
                     const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y,
                     Workspace ws, int epi)
@@ -85,9 +88,10 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // direct load instruction: a block holds 16/KSPG rows, PP = 4*KSPG 16-byte pieces each.
     constexpr int PP = 4 * KSPG;
     constexpr int RPB = 16 / KSPG;         // rows per block
-    constexpr int XBLOCKS = MT * KSPG;     // blocks per chunk
+    constexpr int CBLOCKS = MT * KSPG;     // blocks per chunk
+    constexpr int XBLOCKS = CBLOCKS * KP;  // blocks per iteration (KP consecutive chunks)
     constexpr int XSTAGE = XBLOCKS * 1024;
-    constexpr int WAVES = NW * KW;
+    constexpr int WAVES = NW * KW * KP;
     constexpr int KS = KSPG / KW;                // k-steps of a chunk this wave takes
     static_assert(KS * KW == KSPG, "k-steps divide among a strip's waves");
     constexpr int OX = (XBLOCKS + WAVES - 1) / WAVES;  // direct loads per wave per chunk (at most)
@@ -106,7 +110,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);    // wave-uniform, kept scalar
-    const int wave = wv % NW, kh = wv / NW;                             // strip, and which k-steps of a chunk
+    const int wave = wv % NW, kh = (wv / NW) % KW, ph = wv / (NW * KW);   // strip, which k-steps of a chunk, which chunk of an iteration
     const int lc = lane & 15, lk = lane >> 4;
     const int tile = blockIdx.x;
     const int n0 = tile * BN + wave * 64;
@@ -144,11 +148,20 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // The loading side walks the chunks with wave-uniform byte pointers stepped by constant
     // strides (scalar adds, no multiplies or divisions in the loop).
     const long wstep1 = (long)wrow_stride * 16;                 // one k-step: 4 packed rows, in bytes
-    const unsigned char *wq = reinterpret_cast<const unsigned char *>(packed) + (long)g0 * KSPG * wstep1;
-    const unsigned char *sq = reinterpret_cast<const unsigned char *>(scales) + (long)(g0 / cpg) * N * 2;
-    const unsigned char *zq = zeros + (long)(g0 / cpg) * N;
+    // An iteration covers KP consecutive chunks; this wave's are g0 + ph, g0 + ph + KP, ...  (with
+    // KP = 2 and an odd range the second half of the waves has one chunk fewer; a wave without
+    // any chunk points at g0 and never computes).  The activations are fetched per iteration
+    // for all KP chunks by all waves together.
+    const int nsup = (g1 - g0 + KP - 1) / KP;                    // iterations of this workgroup
+    const bool own_any = g0 + ph < g1;
+    const int cs = own_any ? g0 + ph : g0;                       // this wave's first chunk
+    const int wlast = own_any ? cs + ((g1 - 1 - cs) / KP) * KP : cs;  // and its last
+    const unsigned char *wq = reinterpret_cast<const unsigned char *>(packed) + (long)cs * KSPG * wstep1;
+    const unsigned char *sq = reinterpret_cast<const unsigned char *>(scales) + (long)(cs / cpg) * N * 2;
+    const unsigned char *zq = zeros + (long)(cs / cpg) * N;
     const unsigned char *xq = reinterpret_cast<const unsigned char *>(x) + (long)g0 * (64 * KSPG);
-    int gi = g0, kin = g0 % cpg;                                 // chunk being issued, its position in its group
+    int gi = cs, kin = cs % cpg;                                 // own chunk being issued, its position in its group
+    int xg = g0;                                                 // first chunk of the iteration whose activations are being issued
     // `live` (wave-uniform) is false for the look-ahead loads past the end of the workgroup's range:
     // those are issued with an empty execution mask, so they fetch nothing (with the streaming
     // hint their lines would not be cache hits) and write no register, but still take their
@@ -225,7 +238,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     uint32_t xoff[OX];  // per-lane byte offset into x of each block this wave copies
 #pragma unroll
     for (int i = 0; i < OX; i++) {
-        const int b = (wv + i * WAVES) % XBLOCKS;
+        const int b = ((wv + i * WAVES) % XBLOCKS) % CBLOCKS;   // block within its chunk
         const int row = b * RPB + xrr;
         const int rowc = row < M ? row : M - 1;
         xoff[i] = (uint32_t)rowc * (uint32_t)K * 2u + (uint32_t)((xpp ^ (row % PP)) * 16);
@@ -235,7 +248,10 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         for (int i = 0; i < OX; i++) {
             if (i + 1 == OX && !x_full) break;
             const int b = (wv + i * WAVES) % XBLOCKS;
-            const unsigned char *src = xq + xoff[i];
+            // block b belongs to chunk xg + b / CBLOCKS of the iteration; past the range (the
+            // second chunk of an odd range's last iteration) the first chunk is fetched again
+            const int sub = b / CBLOCKS;
+            const unsigned char *src = xq + (KP > 1 && xg + sub < g1 ? sub * (64 * KSPG) : 0) + xoff[i];
             unsigned char *dst = xring + slot * XSTAGE + b * 1024;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
@@ -246,7 +262,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
 #pragma unroll
     for (int mt = 0; mt < MT; mt++) {
         const int row = mt * 16 + lc;
-        xrd[mt] = (uint32_t)(size_t)xring + (uint32_t)((row / RPB) * 1024 + (row % RPB) * PP * 16);
+        xrd[mt] = (uint32_t)(size_t)xring + (uint32_t)(ph * CBLOCKS * 1024 + (row / RPB) * 1024 + (row % RPB) * PP * 16);
     }
     const int xsw = lc % PP;  // the row's swizzle (16 % PP == 0, so mt does not matter)
 
@@ -361,39 +377,45 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // loads (OX + OW, or one fewer on the waves that copy one block less), and since loads
     // complete in issue order "at most P-1 iterations' worth of loads outstanding" means all but
     // the last P-1 iterations' have landed.  Past the range the pointers stop.
-    const int glast = g1 > g0 ? g1 - 1 : g0;
+    const int xlast = g0 + (nsup > 0 ? nsup - 1 : 0) * KP;  // first chunk of the last iteration
     auto advance = [&]() {
-        const bool more = gi < glast;
-        gi += more ? 1 : 0;
-        wq += more ? KSPG * wstep1 : 0;
-        xq += more ? 64 * KSPG : 0;
-        kin += more ? 1 : 0;
-        const bool wrap = kin == cpg;
-        kin = wrap ? 0 : kin;
-        sq += wrap ? (long)N * 2 : 0;
-        zq += wrap ? (long)N : 0;
+        const bool more = gi < wlast;
+        gi += more ? KP : 0;
+        wq += more ? KP * KSPG * wstep1 : 0;
+        if constexpr (KP == 1) {
+            kin += more ? 1 : 0;
+            const bool wrap = kin == cpg;
+            kin = wrap ? 0 : kin;
+            sq += wrap ? (long)N * 2 : 0;
+            zq += wrap ? (long)N : 0;
+        } else {  // launched only with one chunk per group (cpg == 1)
+            sq += more ? (long)KP * N * 2 : 0;
+            zq += more ? (long)KP * N : 0;
+        }
+        const bool xmore = xg < xlast;
+        xg += xmore ? KP : 0;
+        xq += xmore ? KP * 64 * KSPG : 0;
     };
     Stage st[D];
 #pragma unroll
     for (int j = 0; j < P; j++) {
         issue_x(j);
-        issue_w(st[j], g0 + j < g1);
+        issue_w(st[j], cs + j * KP < g1 && own_any);
         advance();
     }
-    int slot = 0;  // ring slot of chunk g
-    const int nblk = (g1 - g0 + D - 1) / D;
+    int slot = 0;  // ring slot of iteration it
+    const int nblk = (nsup + D - 1) / D;
     for (int b = 0; b < nblk; b++) {
-        const int g = g0 + b * D;
 #pragma unroll
         for (int d = 0; d < D; d++) {
-            const int gg = g + d;
+            const int it = b * D + d;             // iteration; this wave's chunk in it: cs + it * KP
             landed(st[d]);
             asm volatile("s_barrier" ::: "memory");
             const int fill = slot >= 1 ? slot - 1 : XD - 1;  // (slot + P) % XD
             issue_x(fill);
-            issue_w(st[(d + P) % D], gg + P < g1);
+            issue_w(st[(d + P) % D], own_any && cs + (it + P) * KP < g1);
             advance();
-            if (gg < g1) compute(st[d], slot);  // padded iterations only keep the load counts in step
+            if (own_any && cs + it * KP < g1) compute(st[d], slot);  // padded iterations only keep the load counts in step
             slot = slot + 1 == XD ? 0 : slot + 1;
         }
     }
@@ -418,23 +440,29 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // column n0 + 4*(lane%16) + t.
     const int nout = n0 + 4 * lc;
     drain();
-    if constexpr (KW == 2) {
-        // A strip's two waves add their sums: the second wave's go through LDS (the activation
-        // ring is idle once every wave has passed the barrier), then only the first carries on.
-        static_assert(NW * REGS * 256 <= XD * XSTAGE, "the exchange fits the activation ring");
+    constexpr int SENDERS = KW * KP - 1;   // waves per strip beside the one that stores its results
+    const int sid = kh + KW * ph;          // 0: the wave that stores the strip's results
+    if constexpr (SENDERS > 0) {
+        // A strip's waves add their sums: the others' go through LDS (the activation ring is idle
+        // once every wave has passed the barrier) and the first adds them in a fixed order, then
+        // only the first carries on.
+        static_assert(SENDERS * NW * REGS * 256 <= XD * XSTAGE, "the exchange fits the activation ring");
         f32x4 *ex = reinterpret_cast<f32x4 *>(xring) + (size_t)wave * (REGS / 4) * 64 + lane;
+        constexpr int SSTRIDE = NW * (REGS / 4) * 64;  // one sender's strips
         __syncthreads();
-        if (kh == 1) {
+        if (sid != 0) {
 #pragma unroll
-            for (int q = 0; q < REGS / 4; q++) ex[q * 64] = acc[q / 4][q % 4];
+            for (int q = 0; q < REGS / 4; q++) ex[(sid - 1) * SSTRIDE + q * 64] = acc[q / 4][q % 4];
         }
         __syncthreads();
-        if (kh == 0) {
+        if (sid == 0) {
 #pragma unroll
-            for (int q = 0; q < REGS / 4; q++) acc[q / 4][q % 4] += ex[q * 64];
+            for (int sd = 0; sd < SENDERS; sd++)
+#pragma unroll
+                for (int q = 0; q < REGS / 4; q++) acc[q / 4][q % 4] += ex[sd * SSTRIDE + q * 64];
         }
     }
-    const bool lead = kh == 0;  // the wave that stores the strip's results
+    const bool lead = sid == 0;
     if (split == 1) {
         if (lead && nout < N) {
 #pragma unroll
@@ -552,8 +580,21 @@ w4a16_generic_kernel(int M, int N, int K, int group, const h16 *__restrict__ x, 
 
 // ---------------------------------------------------------------- launch
 
-// Test/benchmark hook: 1 = never two waves per strip.
+// Test/benchmark hooks: 1 = never two waves per strip; two chunks per iteration: 0 = automatic,
+// 1 = never, 2 = wherever built.
 int g_decode_kw = 0;
+int g_decode_kp = 0;
+
+// Two chunks per iteration (the kernel's KP = 2, twice the waves: two per SIMD where the launch
+// has one workgroup per compute unit) pays once a workgroup walks at least 16 chunks: 5-8 %
+// on the narrow 34B layers, a loss on ranges of 4 to 11 chunks (7B / 13B shapes), where the pipeline
+// of three iterations in flight is mostly ramp.
+static bool two_chunks(int chunks, int split)
+{
+    if (g_decode_kp == 1) return false;
+    if (g_decode_kp == 2) return true;
+    return chunks / split >= 16;
+}
 
 // The split a launch really runs with (at most one part per chunk; none when the layer has
 // more tiles than the workspace has tickets: such a layer fills the chip anyway) and the
@@ -587,11 +628,23 @@ int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t
     // compute unit: two waves per strip (see the kernel's KW)
     if constexpr (MT <= 2 && KSPG == 4 && NW == 2) {
         if (g_decode_kw != 1 && tiles * split <= 256) {
-            w4a16_decode_kernel<MT, NW, KSPG, 2><<<dim3(tiles, split), NW * 2 * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
+            if constexpr (MT == 1) {
+                if (cpg == 1 && two_chunks(K / 128, split)) {  // and two chunks per iteration: eight waves
+                    w4a16_decode_kernel<MT, NW, KSPG, 2, 2><<<dim3(tiles, split), NW * 4 * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
+                    return sqp_launch_status();
+                }
+            }
+            w4a16_decode_kernel<MT, NW, KSPG, 2, 1><<<dim3(tiles, split), NW * 2 * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
             return sqp_launch_status();
         }
     }
-    w4a16_decode_kernel<MT, NW, KSPG, 1><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
+    if constexpr (MT == 1 && KSPG == 4 && NW == 4) {
+        if (cpg == 1 && tiles * split <= 256 && two_chunks(K / 128, split)) {
+            w4a16_decode_kernel<MT, NW, KSPG, 1, 2><<<dim3(tiles, split), NW * 2 * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
+            return sqp_launch_status();
+        }
+    }
+    w4a16_decode_kernel<MT, NW, KSPG, 1, 1><<<dim3(tiles, split), NW * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
     return sqp_launch_status();
 }
 
@@ -613,7 +666,10 @@ struct Plan {
 // partial tiles are twice as large and it wins up to 40 tiles whatever K.  Without the two-wave
 // variant, two strips only pay where 256 four-strip workgroups would get fewer than eight
 // chunks each.
-Plan make_plan(int M, int N, int K, int chunk)
+// kp_ok: the launch can take two chunks per iteration (up to 16 rows, groups of 128); then a
+// layer of 33 to 40 four-strip tiles also runs best in two-strip workgroups with half the split
+// (8192->10240: 80 tiles x 3 instead of 40 x 6), if that leaves each at least 16 chunks.
+Plan make_plan(int M, int N, int K, int chunk, bool kp_ok)
 {
     const int chunks = K / chunk;
     int max_split = chunks / 4;  // at least four chunks per workgroup
@@ -630,7 +686,8 @@ Plan make_plan(int M, int N, int K, int chunk)
     const int split2 = split_for((N + 127) / 128);
     const bool two_waves = M <= 32 && chunk == 128;  // the launch will give each strip two waves
     bool two_strips;
-    if (two_waves && M <= 16) two_strips = tiles4 <= 32 && chunks <= 24 * split2;
+    if (two_waves && M <= 16)
+        two_strips = chunks <= 24 * split2 && (tiles4 <= 32 || (kp_ok && g_decode_kp != 1 && tiles4 <= 40 && chunks / split2 >= 16));
     else if (two_waves) two_strips = tiles4 <= 40;  // 17..32 rows: partial tiles twice as large, so also with a long K
     else two_strips = tiles4 <= 24 && chunks < 8 * (256 / tiles4);
     if (two_strips) {
@@ -672,6 +729,7 @@ static Plan g_force_plan = {0, 0};
 extern "C" void sqp_debug_set_decode_split(int split) { g_force_split = split; }
 extern "C" void sqp_debug_set_decode_plan(int nw, int split) { g_force_plan = Plan{nw, split}; }
 extern "C" void sqp_debug_set_decode_kw(int kw) { g_decode_kw = kw; }
+extern "C" void sqp_debug_set_decode_kp(int kp) { g_decode_kp = kp; }
 static int g_slice_mode = 0;
 extern "C" void sqp_debug_set_decode_slice(int mode) { g_slice_mode = mode; }
 
@@ -709,7 +767,7 @@ int sqp_gemm_generic(int M, int N, int K, int group, const h16 *x, const uint32_
 extern "C" void sqp_debug_decode_plan(int M, int N, int K, int group, int *nw, int *split, int *kspg)
 {
     const int chunk = group % 128 == 0 ? 128 : group;
-    const Plan p = make_plan(M, N, K, chunk);
+    const Plan p = make_plan(M, N, K, chunk, M <= 16 && group == 128);
     *nw = p.nw;
     *split = p.split;
     *kspg = group == 32 ? 1 : (group == 64 ? 2 : (group % 128 == 0 ? 4 : 0));
@@ -720,7 +778,7 @@ extern "C" void sqp_debug_decode_plan(int M, int N, int K, int group, int *nw, i
 static Plan plan_for(int M, int N, int K, int group, bool have_workspace)
 {
     const int chunk = group % 128 == 0 ? 128 : group;
-    Plan p = make_plan(M, N, K, chunk);
+    Plan p = make_plan(M, N, K, chunk, M <= 16 && group == 128);
     if (g_force_plan.nw > 0) p = g_force_plan;
     if (g_force_split > 0) p.split = g_force_split;
     if (!have_workspace) p.split = 1;

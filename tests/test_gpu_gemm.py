@@ -263,6 +263,28 @@ def test_decode_other_strip_counts(orc, sqp, M, K, N, group, nw, split):
         L.sqp_debug_set_decode_plan(0, 0)
 
 
+@pytest.mark.parametrize("nw,split", [(2, 1), (2, 3), (2, 5), (4, 1), (4, 2), (4, 3)])
+@pytest.mark.parametrize("M,K,N", [(16, 2048, 328), (7, 1152, 1032), (1, 128 * 13, 520), (16, 128, 264)])
+def test_decode_two_chunks_per_iteration(orc, sqp, M, K, N, nw, split):
+    """The strip kernel with two chunks per iteration (twice the waves, each half of them taking
+    every other chunk): even and odd chunk ranges, ranges shorter than the pipeline, a single
+    chunk (the second half of the waves has nothing to do); repeated runs are bit-identical."""
+    print("case two chunks", M, K, N, nw, split, flush=True)
+    xs, p, sc, z = _layer(orc, M, K, N, 128)
+    L = sqp.lib()
+    L.sqp_debug_set_decode_plan(nw, split)
+    L.sqp_debug_set_decode_kp(2)
+    L.sqp_debug_set_decode_slice(-1)
+    try:
+        y0 = _check(orc, sqp, xs, p, sc, z, 128)
+        y1 = _check(orc, sqp, xs, p, sc, z, 128)
+        assert np.array_equal(y0.view(np.uint16), y1.view(np.uint16))
+    finally:
+        L.sqp_debug_set_decode_plan(0, 0)
+        L.sqp_debug_set_decode_kp(0)
+        L.sqp_debug_set_decode_slice(0)
+
+
 @pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("M,K,N", [
     (1, 128, 8), (3, 256, 40), (5, 1152, 72), (16, 384, 520), (7, 1024, 1032), (16, 1536, 2056), (9, 128 * 7, 200),
