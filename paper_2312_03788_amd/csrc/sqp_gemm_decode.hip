@@ -483,7 +483,9 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // is the ticket taken.  Layout: [tile][split][wave][Q][lane][4] floats (each instruction
     // moves 1 KB contiguous per wave).
     constexpr int Q = REGS / 4;                         // 16-byte pieces per lane
-    constexpr int SB = MT == 1 ? 6 : 32 / Q;            // partials fetched per round trip (what fits the register budget without spilling)
+    // partials fetched per round trip: what fits the register budget without spilling (the
+    // variants with two waves per SIMD have 256 registers, so a split of 8 takes one round trip)
+    constexpr int SB = MT == 1 ? (KW * KP >= 2 ? 8 : 6) : 32 / Q;
     {
         float *mine = ws.partial + (((size_t)tile * split + sidx) * NW + wave) * (64 * REGS) + lane * 4;
 #pragma unroll
