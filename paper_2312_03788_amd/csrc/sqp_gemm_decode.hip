@@ -739,18 +739,19 @@ extern "C" void sqp_debug_set_decode_slice(int mode) { g_slice_mode = mode; }
 // slices, 1: 64-column slices).  From sweeps on Code Llama shapes: the slice kernel has no
 // hand-over between workgroups, but every workgroup fetches all of x from L2, and that traffic
 // (workgroups x fetched rows x K) is what it costs.  It wins up to 8 rows (a third to a half of
-// the activation traffic of 16 rows) and, where the strip kernel is furthest from its roofline
-// (narrow layers, short K), up to 12: 64-column slices from 150 slices on (9 to 12 rows: up to
-// 400 slices); below that 32-column slices, unless K is long and the slices are few (then the
-// activations dominate again; 9 to 12 rows: only with K up to 8192).
+// the activation traffic of 16 rows at K = 8192) and beyond that where x is small (short K) and
+// the strip kernel is furthest from its roofline (narrow layers): 64-column slices from 150
+// slices on (more than 8 rows: up to 128 KB of x per workgroup, or up to 192 KB and at most 400
+// slices); below that 32-column slices, unless K is long and the slices are few (then the
+// activations dominate again; 9 to 12 rows: only with K up to 8192, 13 to 16: up to 4096).
 static int slice_variant(int M, int N, int K, int group)
 {
     if (g_slice_mode < 0 || !sqp_gemm_slice_covers(M, N, K, group)) return -1;
     if (g_slice_mode > 0) return g_slice_mode - 1;
-    if (M > 12) return -1;
+    const long xbytes = 4L * ((M + 3) / 4) * K * 2;  // activations a workgroup fetches
     const int slices64 = (N + 63) / 64, slices32 = (N + 31) / 32;
-    if (slices64 >= 150) return (M <= 8 || slices64 <= 400) ? 1 : -1;
-    if (slices32 >= 96 && (slices32 >= 200 || K <= 8192)) return (M <= 8 || K <= 8192) ? 0 : -1;
+    if (slices64 >= 150) return (M <= 8 || xbytes <= (128L << 10) || (xbytes <= (192L << 10) && slices64 <= 400)) ? 1 : -1;
+    if (slices32 >= 96 && (slices32 >= 200 || K <= 8192)) return (M <= 8 || (M <= 12 && K <= 8192) || K <= 4096) ? 0 : -1;
     return -1;
 }
 extern "C" int sqp_debug_decode_slice_choice(int M, int N, int K, int group) { return slice_variant(M, N, K, group); }

@@ -66,8 +66,8 @@ def test_decode_plan_34b_values(L):
 def test_decode_slice_choice(L):
     """Which calls take the column-slice kernel: groups of 128 only; up to 8 rows, 64-column
     slices on the wide layers, 32-column slices on the narrow ones unless K is long and the
-    slices are few; 9 to 12 rows only where the layer is not too wide and K not long; the 16-row
-    calls of the benchmark sweep keep the strip kernel."""
+    slices are few; more than 8 rows only where x is small enough (short K) and the layer not
+    too wide; the 16-row calls of the benchmark sweep (K = 8192 and 22016) keep the strip kernel."""
     L.sqp_debug_decode_slice_choice.restype = ctypes.c_int
     ch = lambda M, K, N, g=128: L.sqp_debug_decode_slice_choice(M, N, K, g)
     assert [ch(1, K, N) for (K, N) in wl.MODEL_SHAPES["34b"]] == [1, 0, 1, 0]
@@ -75,8 +75,10 @@ def test_decode_slice_choice(L):
     assert [ch(1, K, N) for (K, N) in wl.MODEL_SHAPES["13b"]] == [1, 0, 1, -1]
     assert [ch(4, K, N) for (K, N) in wl.MODEL_SHAPES["7b"]] == [1, 0, 1, -1]
     assert [ch(12, K, N) for (K, N) in wl.MODEL_SHAPES["34b"]] == [1, 0, -1, -1]
-    assert [ch(9, K, N) for (K, N) in wl.MODEL_SHAPES["13b"]] == [1, 0, -1, -1]
+    assert [ch(9, K, N) for (K, N) in wl.MODEL_SHAPES["13b"]] == [1, 0, 1, -1]
     assert [ch(12, K, N) for (K, N) in wl.MODEL_SHAPES["7b"]] == [1, 0, 1, -1]
+    assert [ch(16, K, N) for (K, N) in wl.MODEL_SHAPES["7b"]] == [1, 0, 1, -1]      # short K: x is small
+    assert [ch(16, K, N) for (K, N) in wl.MODEL_SHAPES["13b"]] == [1, -1, -1, -1]
     for (K, N) in wl.MODEL_SHAPES["34b"]:
         assert ch(13, K, N) == -1 and ch(16, K, N) == -1 and ch(64, K, N) == -1
         assert ch(1, K, N, 64) == -1 and ch(1, K, N, 256) == -1
