@@ -220,6 +220,37 @@ def test_gemm_outputs_between_guards(orc, sqp, M, K, N, group, with_ws):
         sqp.set_workspace(0)   # through the binding, so that it knows no workspace is set any more
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("M,K,N", [(1, 256, 8), (5, 512, 72), (9, 1152, 200), (16, 2048, 328), (13, 128, 1032), (4, 128 * 9, 48)])
+def test_slice_kernel_outputs_between_guards(orc, sqp, M, K, N, mode):
+    """The column-slice kernel (forced, both slice widths, no workspace set) on ragged M and N:
+    y of the plain and of the fused call stay inside their buffers and meet the tolerance."""
+    print("case guard slice", M, K, N, mode, flush=True)
+    L = sqp.lib()
+    group = 128
+    xs, p, sc, z = _layer(orc, M, K, N, group)
+    dx, dp, dsc, dz = _dev(xs), _dev(p), _dev(sc), _dev(z)
+    y = Guarded(2 * M * N, torch.float16, (M, N))
+    L.sqp_debug_set_decode_slice(mode)
+    try:
+        assert L.sqp_set_workspace(None, ctypes.c_size_t(0), None) == 0
+        assert sqp.workspace_bytes(M, N, K, group) == 0
+        assert _gemm(L, M, N, K, group, dx, dp, dsc, dz, y.ptr) == 0
+        y.check("y")
+        y_ref, t_ref = orc.w4a16_gemm_ref(xs, p, sc, z, group)
+        ok, worst, nbad = gemm_tolerance_ok(orc, y.numpy(), y_ref, t_ref)
+        assert ok, "worst err/tol %.3f, %d elements out of tolerance" % (worst, nbad)
+        if N % 16 == 0:
+            h = Guarded(2 * M * (N // 2), torch.float16, (M, N // 2))
+            st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+            assert L.sqp_w4a16_gemm_silu_mul(M, N, K, group, _ptr(dx), _ptr(dp), _ptr(dsc), _ptr(dz), h.ptr, st) == 0
+            h.check("silu_mul y")
+    finally:
+        torch.cuda.synchronize()
+        L.sqp_debug_set_decode_slice(0)
+        sqp.set_workspace(0)
+
+
 @pytest.mark.parametrize("K,N,group", [(256, 8, 128), (384, 72, 64), (1024, 520, 128), (96, 24, 24), (512, 136, 32), (2048, 1000, 256)])
 def test_companion_outputs_between_guards(orc, sqp, K, N, group):
     """Every output of the companion entry points between guard regions, on ragged shapes;
