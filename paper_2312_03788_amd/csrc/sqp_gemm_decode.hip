@@ -669,8 +669,9 @@ struct Plan {
 // variant, two strips only pay where 256 four-strip workgroups would get fewer than eight
 // chunks each.
 // kp_ok: the launch can take two chunks per iteration (up to 16 rows, groups of 128); then a
-// layer of 33 to 40 four-strip tiles also runs best in two-strip workgroups with half the split
-// (8192->10240: 80 tiles x 3 instead of 40 x 6), if that leaves each at least 16 chunks.
+// layer of up to 40 four-strip tiles runs best in two-strip workgroups with half the split
+// whatever K (8192->10240: 80 tiles x 3 instead of 40 x 6; 22016->8192: 64 x 4 instead of
+// 32 x 8: half the partial tiles), if that leaves each workgroup at least 16 chunks.
 Plan make_plan(int M, int N, int K, int chunk, bool kp_ok)
 {
     const int chunks = K / chunk;
@@ -689,7 +690,7 @@ Plan make_plan(int M, int N, int K, int chunk, bool kp_ok)
     const bool two_waves = M <= 32 && chunk == 128;  // the launch will give each strip two waves
     bool two_strips;
     if (two_waves && M <= 16)
-        two_strips = chunks <= 24 * split2 && (tiles4 <= 32 || (kp_ok && g_decode_kp != 1 && tiles4 <= 40 && chunks / split2 >= 16));
+        two_strips = (tiles4 <= 32 && chunks <= 24 * split2) || (kp_ok && g_decode_kp != 1 && tiles4 <= 40 && chunks / split2 >= 16);
     else if (two_waves) two_strips = tiles4 <= 40;  // 17..32 rows: partial tiles twice as large, so also with a long K
     else two_strips = tiles4 <= 24 && chunks < 8 * (256 / tiles4);
     if (two_strips) {
