@@ -31,8 +31,14 @@
 #include "sqp_common.h"
 #include "sqp_w4_unpack.h"
 
-#ifndef SQP_DECODE_DEPTH
-#define SQP_DECODE_DEPTH 4
+// Pipeline depth (stages of weights per wave, slots of activations): three, i.e. two chunks in
+// flight per wave while one is consumed; the 32-row variant runs best with four.  (With the
+// streaming hint, masked look-ahead loads and up to eight waves per workgroup three beats four by
+// 1-10 % on most shapes; deeper pipelines were slower.)  SQP_DECODE_DEPTH overrides it for experiments.
+#ifdef SQP_DECODE_DEPTH
+#define SQP_DEPTH_OF(MT) SQP_DECODE_DEPTH
+#else
+#define SQP_DEPTH_OF(MT) ((MT) == 2 ? 4 : 3)
 #endif
 
 namespace {
@@ -79,7 +85,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
                     const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y,
                     Workspace ws, int epi)
 {
-    constexpr int D = SQP_DECODE_DEPTH;    // register stages of packed weights
+    constexpr int D = SQP_DEPTH_OF(MT);    // register stages of packed weights
     constexpr int XD = D;                  // LDS slots of activations
     constexpr int P = D - 1;               // chunks in flight ahead of the one being consumed
     constexpr int REGS = MT * 4 * 4;       // fp32 accumulator registers per lane
@@ -105,7 +111,8 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     // in the tiled kernel), so that variant accumulates fp16(w_hat) products directly.
     constexpr bool SCALED_B = MT == 4;
     static_assert((P - 1) * (OX + OW) < 64, "vmcnt field");
-    __shared__ __attribute__((aligned(1024))) unsigned char xring[XD * XSTAGE];
+    constexpr int EXCHANGE = (KW * KP - 1) * NW * REGS * 256;  // bytes of the sums a strip's waves exchange at the end
+    __shared__ __attribute__((aligned(1024))) unsigned char xring[XD * XSTAGE > EXCHANGE ? XD * XSTAGE : EXCHANGE];
     __shared__ unsigned ticket_s;
 
     const int lane = threadIdx.x & 63;
@@ -446,7 +453,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
         // A strip's waves add their sums: the others' go through LDS (the activation ring is idle
         // once every wave has passed the barrier) and the first adds them in a fixed order, then
         // only the first carries on.
-        static_assert(SENDERS * NW * REGS * 256 <= XD * XSTAGE, "the exchange fits the activation ring");
+        static_assert(SENDERS * NW * REGS * 256 == EXCHANGE, "the exchange fits the LDS array");
         f32x4 *ex = reinterpret_cast<f32x4 *>(xring) + (size_t)wave * (REGS / 4) * 64 + lane;
         constexpr int SSTRIDE = NW * (REGS / 4) * 64;  // one sender's strips
         __syncthreads();
