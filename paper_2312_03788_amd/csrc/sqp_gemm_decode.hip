@@ -595,14 +595,14 @@ int g_decode_kw = 0;
 int g_decode_kp = 0;
 
 // Two chunks per iteration (the kernel's KP = 2, twice the waves: two per SIMD where the launch
-// has one workgroup per compute unit) pays once a workgroup walks at least 16 chunks: 5-8 %
-// on the narrow 34B layers, a loss on ranges of 4 to 11 chunks (7B / 13B shapes), where the pipeline
-// of three iterations in flight is mostly ramp.
+// has one workgroup per compute unit) pays once a workgroup walks at least 10 chunks: 5-10 %
+// on the narrow 34B layers and on 11008->4096 / 13824->5120, a loss on ranges of 4 to 7 chunks
+// (4096->4096, 5120->5120), where the pipeline is mostly ramp.
 static bool two_chunks(int chunks, int split)
 {
     if (g_decode_kp == 1) return false;
     if (g_decode_kp == 2) return true;
-    return chunks / split >= 16;
+    return chunks / split >= 10;
 }
 
 // The split a launch really runs with (at most one part per chunk; none when the layer has
@@ -751,7 +751,7 @@ extern "C" void sqp_debug_set_decode_slice(int mode) { g_slice_mode = mode; }
 // the strip kernel is furthest from its roofline (narrow layers): 64-column slices from 150
 // slices on (more than 8 rows: up to 128 KB of x per workgroup, or up to 192 KB and at most 400
 // slices); below that 32-column slices, unless K is long and the slices are few (then the
-// activations dominate again; 9 to 12 rows: only with K up to 8192, 13 to 16: up to 4096).
+// activations dominate again; 5 to 12 rows: only with K up to 8192, 13 to 16: up to 4096).
 static int slice_variant(int M, int N, int K, int group)
 {
     if (g_slice_mode < 0 || !sqp_gemm_slice_covers(M, N, K, group)) return -1;
@@ -759,7 +759,7 @@ static int slice_variant(int M, int N, int K, int group)
     const long xbytes = 4L * ((M + 3) / 4) * K * 2;  // activations a workgroup fetches
     const int slices64 = (N + 63) / 64, slices32 = (N + 31) / 32;
     if (slices64 >= 150) return (M <= 8 || xbytes <= (128L << 10) || (xbytes <= (192L << 10) && slices64 <= 400)) ? 1 : -1;
-    if (slices32 >= 96 && (slices32 >= 200 || K <= 8192)) return (M <= 8 || (M <= 12 && K <= 8192) || K <= 4096) ? 0 : -1;
+    if (slices32 >= 96 && (slices32 >= 200 || K <= 8192)) return (M <= 4 || (M <= 12 && K <= 8192) || K <= 4096) ? 0 : -1;
     return -1;
 }
 extern "C" int sqp_debug_decode_slice_choice(int M, int N, int K, int group) { return slice_variant(M, N, K, group); }

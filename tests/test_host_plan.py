@@ -71,7 +71,8 @@ def test_decode_slice_choice(L):
     L.sqp_debug_decode_slice_choice.restype = ctypes.c_int
     ch = lambda M, K, N, g=128: L.sqp_debug_decode_slice_choice(M, N, K, g)
     assert [ch(1, K, N) for (K, N) in wl.MODEL_SHAPES["34b"]] == [1, 0, 1, 0]
-    assert [ch(8, K, N) for (K, N) in wl.MODEL_SHAPES["34b"]] == [1, 0, 1, 0]
+    assert [ch(4, K, N) for (K, N) in wl.MODEL_SHAPES["34b"]] == [1, 0, 1, 0]
+    assert [ch(8, K, N) for (K, N) in wl.MODEL_SHAPES["34b"]] == [1, 0, 1, -1]     # K = 22016: two blocks of x are too many
     assert [ch(1, K, N) for (K, N) in wl.MODEL_SHAPES["13b"]] == [1, 0, 1, -1]
     assert [ch(4, K, N) for (K, N) in wl.MODEL_SHAPES["7b"]] == [1, 0, 1, -1]
     assert [ch(12, K, N) for (K, N) in wl.MODEL_SHAPES["34b"]] == [1, 0, -1, -1]
