@@ -32,13 +32,14 @@
 #include "sqp_w4_unpack.h"
 
 // Pipeline depth (stages of weights per wave, slots of activations): three, i.e. two chunks in
-// flight per wave while one is consumed; the 32-row variant runs best with four.  (With the
+// flight per wave while one is consumed; the 32-row variant runs best with four (three with two
+// chunks per iteration, whose activation slots are twice as large).  (With the
 // streaming hint, masked look-ahead loads and up to eight waves per workgroup three beats four by
 // 1-10 % on most shapes; deeper pipelines were slower.)  SQP_DECODE_DEPTH overrides it for experiments.
 #ifdef SQP_DECODE_DEPTH
-#define SQP_DEPTH_OF(MT) SQP_DECODE_DEPTH
+#define SQP_DEPTH_OF(MT, KP) SQP_DECODE_DEPTH
 #else
-#define SQP_DEPTH_OF(MT) ((MT) == 2 ? 4 : 3)
+#define SQP_DEPTH_OF(MT, KP) ((MT) == 2 && (KP) == 1 ? 4 : 3)
 #endif
 
 namespace {
@@ -85,7 +86,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
                     const h16 *__restrict__ scales, const uint8_t *__restrict__ zeros, h16 *__restrict__ y,
                     Workspace ws, int epi)
 {
-    constexpr int D = SQP_DEPTH_OF(MT);    // register stages of packed weights
+    constexpr int D = SQP_DEPTH_OF(MT, KP);  // register stages of packed weights
     constexpr int XD = D;                  // LDS slots of activations
     constexpr int P = D - 1;               // chunks in flight ahead of the one being consumed
     constexpr int REGS = MT * 4 * 4;       // fp32 accumulator registers per lane
@@ -113,6 +114,7 @@ w4a16_decode_kernel(int M, int N, int K, int cpg, const h16 *__restrict__ x, con
     static_assert((P - 1) * (OX + OW) < 64, "vmcnt field");
     constexpr int EXCHANGE = (KW * KP - 1) * NW * REGS * 256;  // bytes of the sums a strip's waves exchange at the end
     __shared__ __attribute__((aligned(1024))) unsigned char xring[XD * XSTAGE > EXCHANGE ? XD * XSTAGE : EXCHANGE];
+    static_assert(sizeof(xring) + 16 <= 65536, "static LDS of a workgroup");
     __shared__ unsigned ticket_s;
 
     const int lane = threadIdx.x & 63;
@@ -637,7 +639,7 @@ int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t
     // compute unit: two waves per strip (see the kernel's KW)
     if constexpr (MT <= 2 && KSPG == 4 && NW == 2) {
         if (g_decode_kw != 1 && tiles * split <= 256) {
-            if constexpr (MT == 1) {
+            {
                 if (cpg == 1 && two_chunks(K / 128, split)) {  // and two chunks per iteration: eight waves
                     w4a16_decode_kernel<MT, NW, KSPG, 2, 2><<<dim3(tiles, split), NW * 4 * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
                     return sqp_launch_status();
@@ -647,7 +649,7 @@ int launch(int M, int N, int K, int cpg, int split, const h16 *x, const uint32_t
             return sqp_launch_status();
         }
     }
-    if constexpr (MT == 1 && KSPG == 4 && NW == 4) {
+    if constexpr (MT <= 2 && KSPG == 4 && NW == 4) {
         if (cpg == 1 && tiles * split <= 256 && two_chunks(K / 128, split)) {
             w4a16_decode_kernel<MT, NW, KSPG, 1, 2><<<dim3(tiles, split), NW * 2 * 64, 0, st>>>(M, N, K, cpg, x, packed, scales, zeros, y, ws, epi);
             return sqp_launch_status();

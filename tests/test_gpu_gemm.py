@@ -264,10 +264,10 @@ def test_decode_other_strip_counts(orc, sqp, M, K, N, group, nw, split):
 
 
 @pytest.mark.parametrize("nw,split", [(2, 1), (2, 3), (2, 5), (4, 1), (4, 2), (4, 3)])
-@pytest.mark.parametrize("M,K,N", [(16, 2048, 328), (7, 1152, 1032), (1, 128 * 13, 520), (16, 128, 264)])
+@pytest.mark.parametrize("M,K,N", [(16, 2048, 328), (7, 1152, 1032), (1, 128 * 13, 520), (16, 128, 264), (32, 2048, 328), (19, 1152, 520)])
 def test_decode_two_chunks_per_iteration(orc, sqp, M, K, N, nw, split):
     """The strip kernel with two chunks per iteration (twice the waves, each half of them taking
-    every other chunk): even and odd chunk ranges, ranges shorter than the pipeline, a single
+    every other chunk; the 16- and the 32-row variant): even and odd chunk ranges, ranges shorter than the pipeline, a single
     chunk (the second half of the waves has nothing to do); repeated runs are bit-identical."""
     print("case two chunks", M, K, N, nw, split, flush=True)
     xs, p, sc, z = _layer(orc, M, K, N, 128)
