@@ -119,7 +119,9 @@ int sqp_dequantize(int N, int K, int group, const uint32_t *packed, const void *
  * Rows M <= 64 take the weight-streaming (memory-bound) path, larger M the tiled
  * matrix-core path.  When the output has too few tiles to occupy the chip, the launch plan
  * splits the inner dimension across workgroups and passes fp32 partial sums through the
- * workspace set with sqp_set_workspace:
+ * workspace set with sqp_set_workspace (with few rows, or few rows and a short K, groups of 128
+ * run a kernel that splits K inside each workgroup instead and uses no workspace:
+ * sqp_w4a16_gemm_workspace_bytes() is 0 for those shapes):
  *   - no workspace set: the plan without a split runs (same result within the tolerance of
  *     Eq. 3's fp32 accumulation, slower on narrow layers);
  *   - workspace smaller than sqp_w4a16_gemm_workspace_bytes() of the shape:
