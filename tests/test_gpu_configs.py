@@ -82,13 +82,18 @@ def test_cfg3_13b_shapes(orc, sqp, shape_idx):
 
 @pytest.mark.parametrize("shape_idx", [0, 1, 2, 3])
 def test_cfg4_cfg5_34b_shapes(orc, sqp, shape_idx):
-    """Code Llama-34B layer shapes: M in {1, 16, 64} full output, M in {256, 2048, 4096}
-    sampled."""
+    """Code Llama-34B layer shapes: M in {1, 16, 64} (and 4, 8, 32) full output, M in
+    {256, 2048, 4096} sampled."""
     K, N = wl.MODEL_SHAPES["34b"][shape_idx]
     print("case 34b", K, N, flush=True)
     s, p, sc, z = _quantised_layer(orc, K, N, shape_idx)
     dq = (dev(p), dev(sc), dev(z))
     for M in (1, 16, 64):
+        print("  M", M, flush=True)
+        _full_parity(orc, sqp, s, p, sc, z, dq, M, K)
+    # beside the named row counts: the other kernels a small batch takes at this size
+    # (4 and 8 rows: column slices or strips, 32 rows: the 32-row strip variant)
+    for M in (4, 8, 32):
         print("  M", M, flush=True)
         _full_parity(orc, sqp, s, p, sc, z, dq, M, K)
     for M in [256] + wl.PREFILL_M:
