@@ -86,6 +86,21 @@ def test_decode_slice_choice(L):
     assert ch(1, 4096, 1024) == -1 and ch(1, 128, 8) == -1      # few slices: the strip kernel and its K split
 
 
+def test_slice_calls_need_no_workspace(L):
+    """A call that takes the column-slice kernel reports no workspace; the 16-row calls of the
+    34B sweep (strip kernel, K split across workgroups) report tickets plus partial sums."""
+    L.sqp_debug_decode_slice_choice.restype = ctypes.c_int
+    L.sqp_w4a16_gemm_workspace_bytes.restype = ctypes.c_size_t
+    for model in ("7b", "13b", "34b"):
+        for (K, N) in wl.MODEL_SHAPES[model]:
+            for M in (1, 4, 8, 12, 16):
+                need = L.sqp_w4a16_gemm_workspace_bytes(M, N, K, 128)
+                if L.sqp_debug_decode_slice_choice(M, N, K, 128) >= 0:
+                    assert need == 0
+    for (K, N) in wl.MODEL_SHAPES["34b"]:
+        assert L.sqp_w4a16_gemm_workspace_bytes(16, N, K, 128) > 512 << 10
+
+
 def test_decode_plan_many_rows(L):
     """More than 32 rows: two strips per workgroup, the split of the 16-row plan."""
     for (K, N) in wl.MODEL_SHAPES["34b"]:
